@@ -1,0 +1,148 @@
+/* libknapattn: packed variable-length joint self-attention for MI355X (gfx950),
+ * forward and backward, plus the host-side workload model and greedy balancer
+ * of KnapFormer (arXiv 2508.06001).
+ *
+ * Plain C ABI.  No C++ or framework types cross this boundary.
+ *
+ * Conventions for every function that returns int: 0 (KNAP_OK) on success, a
+ * negative KNAP_ERR_* otherwise.  Nothing aborts, throws or prints.
+ */
+#ifndef KNAPATTN_H
+#define KNAPATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KNAP_OK                        0
+#define KNAP_ERR_INVALID_ARG          -1  /* null pointer, bad size, unsupported head dim, misaligned pointer */
+#define KNAP_ERR_WORKSPACE_TOO_SMALL  -2
+#define KNAP_ERR_LAUNCH_FAILED        -3  /* the HIP runtime refused a launch; see knap_last_hip_error() */
+#define KNAP_ERR_TOO_MANY_SEQS        -4  /* n_seq above KNAP_MAX_SEQS */
+#define KNAP_ERR_CAPACITY             -5  /* an output array of a host function is too small */
+#define KNAP_ERR_PARSE                -6  /* malformed topology string */
+
+/* Largest number of sequences in one packed bag.  Every workgroup rebuilds the
+ * tile schedule from cu_seqlens in LDS, which bounds the bag size. */
+#define KNAP_MAX_SEQS 2048
+
+/* ------------------------------------------------------------------------
+ * Attention.  Defined by Sec. 3.4 and the attention listing of Sec. 3.5 of
+ * the paper: packed q, k, v of shape (l1+...+ln, h, d) and the list of
+ * sequence lengths; each sequence attends only to itself (bidirectional, no
+ * mask inside a sequence; "Limitations" paragraph).  Eq. 1's 4 l^2 d term is
+ * this operation's FLOP count.
+ *
+ * Layout.  q, k, v, out, dout, dq, dk, dv: bf16, shape (T, H, d), d fastest,
+ * contiguous, T = cu_seqlens[n_seq].  lse: fp32, shape (H, T): the natural
+ * log of sum_j exp(scale * q_i . k_j) over the keys of row i's sequence.
+ * cu_seqlens: int32[n_seq + 1], cu[0] = 0, non-decreasing (zero-length
+ * sequences are legal and skipped).  Its contents live on the device and are
+ * NOT validated (that would need a synchronisation): a non-monotone array is
+ * a caller error with undefined results.
+ *
+ * Memory.  Every pointer is a DEVICE pointer owned by the caller, 16-byte
+ * aligned.  The library never allocates, frees or synchronises: all work is
+ * enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ * stream) and the call returns at once.  Outputs are fully overwritten for
+ * rows < T; inputs are never modified; outputs must not alias inputs.
+ *
+ * Supported: d in {64, 128}; 0 <= n_seq <= KNAP_MAX_SEQS; H >= 1.
+ * n_seq == 0 succeeds and enqueues nothing.
+ * ------------------------------------------------------------------------ */
+
+/* out = softmax(scale * q k^T) v per (sequence, head); also writes lse. */
+int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, int n_seq,
+                         int H, int d, float scale,
+                         void* out, float* lse,
+                         void* stream);
+
+/* Gradients of sum(dout * out) with respect to q, k, v, recomputing the
+ * probabilities from q, k and lse (as produced by the forward call).
+ *
+ * `total_tokens` must equal cu_seqlens[n_seq]; it sizes the launches and the
+ * workspace because the host cannot read cu_seqlens without synchronising.
+ * `workspace` is caller-owned device scratch of at least
+ * knap_varlen_attn_bwd_workspace_bytes(total_tokens, n_seq, H, d) bytes,
+ * 256-byte aligned; its contents on entry are ignored and on return are
+ * unspecified. */
+int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, int n_seq,
+                         int H, int d, float scale,
+                         const void* out, const float* lse,
+                         const void* dout,
+                         void* dq, void* dk, void* dv,
+                         int64_t total_tokens,
+                         void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d);
+
+/* Message for a KNAP_ERR_* code (static string, never NULL). */
+const char* knap_strerror(int code);
+
+/* The hipError_t (as int) of the most recent failed launch on this thread, 0 if none. */
+int knap_last_hip_error(void);
+
+/* Number of persistent workgroups the forward / backward kernels are launched
+ * with on the current device (for benchmarks and tests; <= 0 on error). */
+int knap_launch_workgroups(int which /* 0 = forward, 1 = backward */);
+
+/* ------------------------------------------------------------------------
+ * Host-side workload model and balancer (pure C, host pointers, no GPU).
+ * ------------------------------------------------------------------------ */
+
+/* a L^2 + b L: the semi-empirical per-sequence cost (Sec. 3.1, Eq. 2 with
+ * a = k gamma 4 d and b = k 24 d^2). */
+double knap_seq_cost(int64_t L, double a, double b);
+
+/* 24 l d^2 + gamma 4 l^2 d with d = d_model (Eq. 1 for gamma = 1, Eq. 2
+ * without the hardware constant otherwise). */
+double knap_flux_workload(int64_t l, int64_t d_model, double gamma);
+
+/* Fit t ~ a sumL2 + b sumL over n measurements by least squares on the
+ * relative error, no intercept (Sec. 3.1: the correction is obtained by
+ * fitting the model to measured (l, t) pairs).  Writes a, b and the largest
+ * relative residual.  n >= 2, every t > 0. */
+int knap_fit_cost_model(const double* sum_l2, const double* sum_l, const double* t, int n,
+                        double* a, double* b, double* max_rel_resid);
+
+/* "g1n2+g2n1+g4n1" -> bag_gpus = {1, 1, 2, 4}, *n_bags = 4 (Sec. 3.2).
+ * `cap` is the capacity of bag_gpus. */
+int knap_parse_topology(const char* spec, int* bag_gpus, int cap, int* n_bags);
+
+/* First pass of the greedy balancer (Sec. 3.3) with cost a L^2 + b L:
+ * sequences in descending cost (stable), each to the bag of lowest occupancy
+ * among those with enough remaining capacity; if none has, among all bags.
+ * Writes bag_of_seq[n_seq] and bag_load[n_bags]. */
+int knap_greedy_assign(const int64_t* seq_len, int n_seq,
+                       const int* bag_gpus, int n_bags,
+                       double a, double b,
+                       int* bag_of_seq, double* bag_load);
+
+/* The same pass on caller-computed weights (e.g. knap_flux_workload). */
+int knap_greedy_assign_weights(const double* weight, int n_seq,
+                               const int* bag_gpus, int n_bags,
+                               int* bag_of_seq, double* bag_load);
+
+/* Second pass (Sec. 3.3): lengths of the g contiguous chunks of a sequence,
+ * the first (L mod g) one token longer.  Writes chunk_len[g]. */
+int knap_chunk_lengths(int64_t L, int g, int64_t* chunk_len);
+
+/* Workload imbalance ratio (Sec. 4.2): max / min over bags of load_j / gpus_j. */
+double knap_wir(const double* bag_load, const int* bag_gpus, int n_bags);
+
+/* Packed list of one bag: writes the lengths of the sequences assigned to
+ * `bag` (original order) to out_len[cap], their count to *n_out, and, if
+ * cu_seqlens is not NULL, their prefix sums to cu_seqlens[*n_out + 1]. */
+int knap_bag_cu_seqlens(const int64_t* seq_len, const int* bag_of_seq, int n_seq, int bag,
+                        int64_t* out_len, int cap, int* n_out, int32_t* cu_seqlens);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNAPATTN_H */

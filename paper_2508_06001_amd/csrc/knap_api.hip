@@ -1,0 +1,137 @@
+// C-ABI entry points of libknapattn: argument checks, workspace carving and
+// launches.  Nothing here allocates, frees or synchronises.
+#include "knapattn.h"
+#include "knap_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+struct DeviceInfo {
+  int cus = 0;
+  int fwd_wg[2] = {0, 0};   // workgroups per CU, index 0: d = 64, 1: d = 128
+  int bwd_wg[2] = {0, 0};
+};
+
+// per-device launch geometry, filled on first use (occupancy queries do not allocate)
+DeviceInfo* device_info() {
+  static DeviceInfo info[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return nullptr; }
+  DeviceInfo& di = info[dev];
+  if (di.cus == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
+    di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
+    di.bwd_wg[0] = knap::bwd_workgroups_per_cu(64);
+    di.bwd_wg[1] = knap::bwd_workgroups_per_cu(128);
+    di.cus = cus;
+  }
+  return &di;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_common(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d) {
+  if (n_seq < 0 || H <= 0 || (d != 64 && d != 128)) return KNAP_ERR_INVALID_ARG;
+  if (n_seq > KNAP_MAX_SEQS) return KNAP_ERR_TOO_MANY_SEQS;
+  if (n_seq == 0) return KNAP_OK;
+  if (!q || !k || !v || !cu) return KNAP_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(cu, 4)) return KNAP_ERR_INVALID_ARG;
+  return KNAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, int n_seq,
+                         int H, int d, float scale,
+                         void* out, float* lse, void* stream) {
+  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d);
+  if (rc != KNAP_OK) return rc;
+  if (n_seq == 0) return KNAP_OK;
+  if (!out || !lse || !aligned(out, 16) || !aligned(lse, 4)) return KNAP_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return KNAP_ERR_INVALID_ARG;
+  DeviceInfo* di = device_info();
+  if (!di) return KNAP_ERR_LAUNCH_FAILED;
+  const int grid = di->cus * di->fwd_wg[d == 128];
+  const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, grid,
+                                        static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
+  return KNAP_OK;
+}
+
+size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d) {
+  (void)n_seq;
+  if (total_tokens <= 0 || H <= 0 || d <= 0) return 0;
+  const size_t delta = round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256);
+  const size_t dq_acc = round_up(static_cast<size_t>(total_tokens) * H * d * sizeof(float), 256);
+  return delta + dq_acc;
+}
+
+int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, int n_seq,
+                         int H, int d, float scale,
+                         const void* out, const float* lse, const void* dout,
+                         void* dq, void* dk, void* dv,
+                         int64_t total_tokens,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d);
+  if (rc != KNAP_OK) return rc;
+  if (total_tokens < 0 || total_tokens > INT32_MAX) return KNAP_ERR_INVALID_ARG;
+  if (n_seq == 0 || total_tokens == 0) return KNAP_OK;
+  if (!out || !lse || !dout || !dq || !dk || !dv) return KNAP_ERR_INVALID_ARG;
+  if (!aligned(out, 16) || !aligned(dout, 16) || !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) ||
+      !aligned(lse, 4))
+    return KNAP_ERR_INVALID_ARG;
+  if (dq == dk || dq == dv || dk == dv || dq == q || dk == k || dv == v) return KNAP_ERR_INVALID_ARG;
+  const size_t need = knap_varlen_attn_bwd_workspace_bytes(total_tokens, n_seq, H, d);
+  if (!workspace || !aligned(workspace, 256)) return KNAP_ERR_INVALID_ARG;
+  if (workspace_bytes < need) return KNAP_ERR_WORKSPACE_TOO_SMALL;
+  DeviceInfo* di = device_info();
+  if (!di) return KNAP_ERR_LAUNCH_FAILED;
+
+  float* delta = static_cast<float*>(workspace);
+  float* dq_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                           round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256));
+  const int grid = di->cus * di->bwd_wg[d == 128];
+  const int aux_grid = di->cus * 8;
+  const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
+                                        total_tokens, delta, dq_acc, grid, aux_grid,
+                                        static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
+  return KNAP_OK;
+}
+
+const char* knap_strerror(int code) {
+  switch (code) {
+    case KNAP_OK: return "success";
+    case KNAP_ERR_INVALID_ARG: return "invalid argument";
+    case KNAP_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case KNAP_ERR_LAUNCH_FAILED: return "kernel launch failed";
+    case KNAP_ERR_TOO_MANY_SEQS: return "too many sequences in one bag";
+    case KNAP_ERR_CAPACITY: return "output array too small";
+    case KNAP_ERR_PARSE: return "malformed topology string";
+    default: return "unknown error";
+  }
+}
+
+int knap_last_hip_error(void) { return g_last_hip_error; }
+
+int knap_launch_workgroups(int which) {
+  DeviceInfo* di = device_info();
+  if (!di) return -1;
+  return di->cus * (which == 0 ? di->fwd_wg[1] : di->bwd_wg[1]);
+}
+
+}  // extern "C"

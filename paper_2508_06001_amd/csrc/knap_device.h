@@ -1,0 +1,188 @@
+// Device-side building blocks shared by the forward and backward attention
+// kernels: MFMA wrappers, LDS transpose reads, bf16 packing and the tile
+// schedule every persistent workgroup rebuilds from cu_seqlens.
+//
+// gfx950 only.  Lane layouts used throughout (wave64, lane l, hh = l / 32):
+//   v_mfma_f32_32x32x16_bf16   A (32 x 16): lane holds A[l % 32][8 hh + e], e = 0..7
+//                              B (16 x 32): lane holds B[8 hh + e][l % 32]
+//                              D (32 x 32): reg r is D[8 (r / 4) + 4 hh + r % 4][l % 32]
+//   ds_read_b64_tr_b16         per 16-lane block, lane i supplies the address of 4
+//                              consecutive b16 of "row" i; lane i receives element
+//                              (i % 4) of rows 4 e + i / 4, e = 0..3.  Pointing lane i
+//                              at X[k0 + i / 4][n0 + 4 (i % 4)] of a row-major X[k][n]
+//                              therefore returns X[k0 + e][n0 + i]: a 4 x 16 transpose.
+// The contraction index of an MFMA may be permuted freely as long as A and B
+// use the same permutation; the kernels exploit that to feed a D-layout result
+// straight back in as an operand.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace knap {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;   // 4 waves per workgroup
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+__device__ __forceinline__ bf16x8 zero_bf16x8() {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  return __builtin_bit_cast(bf16x8, z);
+}
+
+// 4 x 16 transposing LDS read (see the header comment).
+__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (__attribute__((address_space(3))) bf16x4*)(p));
+}
+
+__device__ __forceinline__ bf16x8 join(bf16x4 lo, bf16x4 hi) {
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// An 8-element MFMA operand whose contraction index runs down a row-major LDS
+// matrix X[k][n] (stride `ld` elements): element e of the lane with column
+// n = n_base + (l % 32) is X[k_lo + e][n] for e < 4 and X[k_hi + e - 4][n] else.
+// `lane` is the lane id; k_lo / k_hi may depend on hh = lane / 32.
+__device__ __forceinline__ bf16x8 lds_operand_tr(const __bf16* X, int ld, int k_lo, int k_hi,
+                                                 int n_base, int lane) {
+  const int i = lane & 15;
+  const int n0 = n_base + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
+  const int kr = i >> 2;
+  bf16x4 lo = lds_read_tr(X + (k_lo + kr) * ld + n0);
+  bf16x4 hi = lds_read_tr(X + (k_hi + kr) * ld + n0);
+  return join(lo, hi);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xor32(float x) {
+  return __shfl_xor(x, 32, 64);
+}
+
+// round-to-nearest-even fp32 -> bf16 (the compiler selects v_cvt_pk_bf16_f32)
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
+                                        float a4, float a5, float a6, float a7) {
+  bf16x8 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+  return r;
+}
+
+__device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
+  bf16x4 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  return r;
+}
+
+// ---------------------------------------------------------------------------
+// Tile schedule.  A work item is (sequence, head, tile of TILE rows).  Items
+// are ordered by sequence length, longest first (an item's cost grows with the
+// length of its sequence), then head, then tile, so that neighbouring items
+// share one (sequence, head)'s K and V.  Every workgroup rebuilds the same
+// schedule in LDS from cu_seqlens; the host never reads cu_seqlens.
+//
+//   s_order[r]  original index of the r-th longest sequence
+//   s_start[r]  first item of that sequence; s_start[n_seq] = number of items
+// s_start doubles as the key array of the rank sort before it is filled.
+// ---------------------------------------------------------------------------
+struct WorkItem {
+  int row0;   // first packed row of the sequence
+  int len;    // its length
+  int head;
+  int tile;
+};
+
+template <int TILE>
+__device__ __forceinline__ int build_schedule(const int32_t* __restrict__ cu, int n_seq, int H,
+                                              int* s_order, int* s_start, int* s_part /* kThreads ints */) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < n_seq; i += kThreads) s_start[i] = cu[i + 1] - cu[i];
+  __syncthreads();
+  // rank sort, descending length, ties by original index
+  for (int i = tid; i < n_seq; i += kThreads) {
+    const int li = s_start[i];
+    int rank = 0;
+    for (int j = 0; j < n_seq; ++j) {
+      const int lj = s_start[j];
+      rank += (lj > li) || (lj == li && j < i);
+    }
+    s_order[rank] = i;
+  }
+  __syncthreads();
+  // exclusive prefix sum of items per sequence, in sorted order
+  const int chunk = (n_seq + kThreads - 1) / kThreads;
+  const int lo = min(tid * chunk, n_seq), hi = min(lo + chunk, n_seq);
+  int local = 0;
+  for (int r = lo; r < hi; ++r) {
+    const int s = s_order[r];
+    local += ((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
+  }
+  s_part[tid] = local;
+  __syncthreads();
+  for (int off = 1; off < kThreads; off <<= 1) {
+    const int add = tid >= off ? s_part[tid - off] : 0;
+    __syncthreads();
+    s_part[tid] += add;
+    __syncthreads();
+  }
+  int run = s_part[tid] - local;   // exclusive
+  for (int r = lo; r < hi; ++r) {
+    const int s = s_order[r];
+    s_start[r] = run;
+    run += ((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
+  }
+  if (tid == kThreads - 1) s_start[n_seq] = s_part[kThreads - 1];
+  __syncthreads();
+  return s_start[n_seq];
+}
+
+template <int TILE>
+__device__ __forceinline__ WorkItem decode_item(int w, const int32_t* __restrict__ cu, int n_seq,
+                                                const int* s_order, const int* s_start) {
+  // largest r with s_start[r] <= w (sequences without items share their successor's start)
+  int lo = 0, hi = n_seq - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (s_start[mid] <= w) lo = mid; else hi = mid - 1;
+  }
+  const int s = s_order[lo];
+  WorkItem it;
+  it.row0 = cu[s];
+  it.len = cu[s + 1] - it.row0;
+  const int tiles = (it.len + TILE - 1) / TILE;
+  const int rem = w - s_start[lo];
+  it.head = rem / tiles;
+  it.tile = rem - it.head * tiles;
+  return it;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by blockIdx.  Renumber them
+// so that the workgroups of one XCD take neighbouring work items and meet in
+// that XCD's L2 on the same K and V.
+__device__ __forceinline__ int xcd_major_block_id() {
+  const int g = gridDim.x;
+  const int b = blockIdx.x;
+  return (g % 8 == 0) ? (b % 8) * (g / 8) + b / 8 : b;
+}
+
+}  // namespace knap

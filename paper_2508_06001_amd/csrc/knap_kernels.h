@@ -1,0 +1,21 @@
+// Internal launch interface between the C-ABI layer and the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace knap {
+
+hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
+                      int H, int d, float scale, void* out, float* lse, int grid, hipStream_t stream);
+
+hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
+                      float scale, const void* out, const float* lse, const void* dout,
+                      void* dq, void* dk, void* dv, int64_t T, float* delta, float* dq_acc,
+                      int grid, int aux_grid, hipStream_t stream);
+
+// resident workgroups per compute unit of the persistent kernels
+int fwd_workgroups_per_cu(int d);
+int bwd_workgroups_per_cu(int d);
+
+}  // namespace knap

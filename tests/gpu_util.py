@@ -1,0 +1,69 @@
+"""Helpers for the GPU parity tests: run the HIP path on seeded inputs and bring
+the results back as float64 numpy arrays.  No oracle input or expected value is
+ever taken from here."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+
+from knap_inputs import BagSpec, bf16_bits_to_f32, cu_seqlens_of, make_qkv_dout
+
+
+def say(msg: str) -> None:
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_f64(bits: np.ndarray) -> np.ndarray:
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+class GpuRun:
+    """q, k, v, dout on the device, one forward and one backward through the C ABI."""
+
+    def __init__(self, bag: BagSpec, tensors=None, backward: bool = True):
+        import torch
+        import paper_2508_06001_amd as K
+        from paper_2508_06001_amd.runtime import bf16_bits_to_device, bf16_device_to_bits
+
+        self.bag = bag
+        self.bits = tensors if tensors is not None else make_qkv_dout(bag)
+        self.cu = cu_seqlens_of(bag.seq_lens)
+        say(f"[gpu] bag={bag.name} seed={bag.seed} n_seq={len(bag.seq_lens)} T={bag.total_tokens} "
+            f"H={bag.H} d={bag.d} maxL={max(bag.seq_lens) if bag.seq_lens else 0}")
+        dev = {n: bf16_bits_to_device(self.bits[n]) for n in ("q", "k", "v", "dout")}
+        self.dev = dev
+        self.attn = K.VarlenAttention(self.cu, bag.H, bag.d, bag.scale)
+        # canaries: outputs start as NaN so an unwritten element cannot pass
+        self.attn.out.fill_(float("nan"))
+        self.attn.lse.fill_(float("nan"))
+        say("[gpu] forward")
+        self.attn.forward(dev["q"], dev["k"], dev["v"])
+        torch.cuda.synchronize()
+        self.out_bits = bf16_device_to_bits(self.attn.out)
+        self.lse = self.attn.lse.cpu().numpy().astype(np.float64)
+        if backward:
+            self.attn._ensure_bwd_buffers()
+            for t in (self.attn.dq, self.attn.dk, self.attn.dv):
+                t.fill_(float("nan"))
+            say("[gpu] backward")
+            self.attn.backward(dev["q"], dev["k"], dev["v"], dev["dout"])
+            torch.cuda.synchronize()
+            self.dq_bits = bf16_device_to_bits(self.attn.dq)
+            self.dk_bits = bf16_device_to_bits(self.attn.dk)
+            self.dv_bits = bf16_device_to_bits(self.attn.dv)
+        say("[gpu] done")
+
+    def host(self, name: str, rows: slice, head: int) -> np.ndarray:
+        """float64 view of rows of one head of an input or output tensor."""
+        src = {"out": getattr(self, "out_bits", None), "dq": getattr(self, "dq_bits", None),
+               "dk": getattr(self, "dk_bits", None), "dv": getattr(self, "dv_bits", None)}.get(name)
+        if src is None:
+            src = self.bits[name]
+        return to_f64(src[rows, head, :])
+
+
+def rel_fro(a: np.ndarray, b: np.ndarray) -> float:
+    nb = float(np.linalg.norm(b))
+    return float(np.linalg.norm(a - b)) / (nb if nb > 0 else 1.0)
