@@ -1,0 +1,321 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed variable-length attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-cpu-baseline]
+    python bench.py --fit            # cost-model calibration + per-bag residuals (long; writes a report)
+
+A step is one pass of the whole hot path over one bag: the forward call and the
+backward call through the C ABI, inputs resident in HBM.  Default workload:
+the ~32k-token mixed-resolution image bag (benchmark config 1).  One JSON line
+is printed at the end.
+
+FLOP convention: 14 H d sum(L^2) per step (4 forward + 10 recompute backward;
+Eq. 1's 4 l^2 d per forward); tile padding is never counted.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t pairs from the HIP runtime PyTorch already loaded (RTLD_NOLOAD: never a second runtime)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so.7", mode=os.RTLD_NOLOAD | C.RTLD_GLOBAL)
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self) -> int:
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return ev.value
+
+    def record(self, ev: int, stream: int) -> None:
+        rc = self.hip.hipEventRecord(ev, stream)
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.hip.hipEventDestroy(ev)
+
+
+def flops_fwd(bag) -> float:
+    return 4.0 * bag.H * bag.d * bag.sum_l2
+
+
+def flops_bwd(bag) -> float:
+    return 10.0 * bag.H * bag.d * bag.sum_l2
+
+
+def device_inputs(bag, seed_tensors=True):
+    """bf16 q, k, v, dout on the device.  Values are N(0,1) from the bag's seed (host generator)."""
+    import torch
+    from knap_inputs import make_qkv_dout
+    from paper_2508_06001_amd.runtime import bf16_bits_to_device
+    bits = make_qkv_dout(bag)
+    dev = {n: bf16_bits_to_device(bits[n]) for n in ("q", "k", "v", "dout")}
+    torch.cuda.synchronize()
+    return bits, dev
+
+
+def device_inputs_fast(bag, seed=0):
+    """Same distribution drawn on the device (for sweeps where no oracle comparison is made)."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(bag.seed + seed)
+    shape = (bag.total_tokens, bag.H, bag.d)
+    dev = {}
+    for n in ("q", "k", "v", "dout"):
+        x = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+        if n == "k" and bag.k_outlier_prob > 0:
+            m = torch.rand(shape, generator=g, device="cuda") < bag.k_outlier_prob
+            x = torch.where(m, x * bag.k_outlier_scale, x)
+        dev[n] = x.to(torch.bfloat16)
+        del x
+    return dev
+
+
+def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
+    """Returns dict of per-step ms: total, fwd, bwd (whole call), bwd_main (dominant kernel)."""
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import cu_seqlens_of
+
+    attn = K.VarlenAttention(cu_seqlens_of(bag.seq_lens), bag.H, bag.d, bag.scale)
+    attn._ensure_bwd_buffers()
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    q, k, v, dout = dev["q"], dev["k"], dev["v"], dev["dout"]
+    for _ in range(warmup):
+        attn.forward(q, k, v)
+        attn.backward(q, k, v, dout)
+    torch.cuda.synchronize()
+
+    n_ev = steps
+    e_f0 = [ev.create() for _ in range(n_ev)]
+    e_f1 = [ev.create() for _ in range(n_ev)]
+    e_b1 = [ev.create() for _ in range(n_ev)]
+    e_m0 = [ev.create() for _ in range(n_ev)]
+    e_m1 = [ev.create() for _ in range(n_ev)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev.record(e_f0[i], stream)
+        attn.forward(q, k, v)
+        ev.record(e_f1[i], stream)
+        K.knap_bwd_profile_events(e_m0[i], e_m1[i])
+        attn.backward(q, k, v, dout)
+        ev.record(e_b1[i], stream)
+    K.knap_bwd_profile_events(None, None)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    fwd = [ev.elapsed_ms(e_f0[i], e_f1[i]) for i in range(steps)]
+    bwd = [ev.elapsed_ms(e_f1[i], e_b1[i]) for i in range(steps)]
+    main = [ev.elapsed_ms(e_m0[i], e_m1[i]) for i in range(steps)]
+    span = ev.elapsed_ms(e_f0[0], e_b1[-1])
+    for lst in (e_f0, e_f1, e_b1, e_m0, e_m1):
+        for e in lst:
+            ev.destroy(e)
+    return {
+        "wall_ms_per_step": wall_ms / steps,
+        "gpu_ms_per_step": span / steps,
+        "fwd_ms": float(np.mean(fwd)), "bwd_ms": float(np.mean(bwd)), "bwd_main_ms": float(np.mean(main)),
+        "fwd_ms_min": float(np.min(fwd)), "bwd_ms_min": float(np.min(bwd)),
+        "attn": attn,
+    }
+
+
+def cpu_baseline(bag, bits, budget_s: float = 20.0):
+    """The fp64 oracle, as it stands, on the host cores: forward + backward of whole
+    (sequence, head) units of the same bag, added longest-first-agnostic in bag order
+    for head 0, 1, ... until about `budget_s` seconds of CPU work have been spent."""
+    from knap_inputs import bf16_bits_to_f32
+    from oracle import attention as A
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    cu = np.concatenate([[0], np.cumsum(bag.seq_lens)]).astype(np.int64)
+    done_flops = 0.0
+    units = 0
+    t0 = time.perf_counter()
+    stop = False
+    for h in range(bag.H):
+        for s in range(len(bag.seq_lens)):
+            L = int(bag.seq_lens[s])
+            if L == 0:
+                continue
+            sl = slice(int(cu[s]), int(cu[s + 1]))
+            Q, K_, V, dO = (bf16_bits_to_f32(bits[n][sl, h, :]).astype(np.float64) for n in ("q", "k", "v", "dout"))
+            A.attn_fwd_dense(Q, K_, V, bag.scale)
+            A.attn_bwd_dense(Q, K_, V, dO, bag.scale)
+            done_flops += 14.0 * bag.d * L * L
+            units += 1
+            if time.perf_counter() - t0 > budget_s:
+                stop = True
+                break
+        if stop:
+            break
+    dt = time.perf_counter() - t0
+    return {
+        "value": done_flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{units} (sequence, head) units of the same bag, fwd+bwd, {dt:.1f} s of fp64 numpy",
+    }
+
+
+def run_default(args):
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import config_bag
+
+    bag = config_bag(args.config)
+    log(f"[bench] config {args.config} ({bag.name}): n_seq={len(bag.seq_lens)} T={bag.total_tokens} "
+        f"H={bag.H} d={bag.d} maxL={max(bag.seq_lens)} sumL2={bag.sum_l2:.4g}")
+    if args.config <= 1:
+        bits, dev = device_inputs(bag)
+    else:
+        bits, dev = None, device_inputs_fast(bag)
+    ev = HipEvents()
+    r = time_bag(bag, dev, args.steps, args.warmup, ev)
+    ms = r["gpu_ms_per_step"]
+    total_flops = flops_fwd(bag) + flops_bwd(bag)
+    value = total_flops / (ms * 1e-3) / 1e12
+    bwd_main_tflops = flops_bwd(bag) / (r["bwd_main_ms"] * 1e-3) / 1e12
+    fwd_tflops = flops_fwd(bag) / (r["fwd_ms"] * 1e-3) / 1e12
+    log(f"[bench] ms/step={ms:.3f} (wall {r['wall_ms_per_step']:.3f}) fwd={r['fwd_ms']:.3f} ms ({fwd_tflops:.1f} TF/s) "
+        f"bwd={r['bwd_ms']:.3f} ms, bwd main kernel={r['bwd_main_ms']:.3f} ms ({bwd_main_tflops:.1f} TF/s)")
+    out = {
+        "metric": "varlen attention fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {bag.name}", "n_seq": len(bag.seq_lens),
+                   "total_tokens": bag.total_tokens, "H": bag.H, "d": bag.d, "max_len": max(bag.seq_lens),
+                   "seed": bag.seed, "flops_per_step": total_flops,
+                   "flop_convention": "14*H*d*sum(L^2) (4 fwd + 10 recompute bwd)"},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "paper_convention_tflops": round(value * 12.0 / 14.0, 3),
+        "fwd_ms": round(r["fwd_ms"], 4), "bwd_ms": round(r["bwd_ms"], 4),
+        "fwd_tflops": round(fwd_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_kernel", "achieved": round(bwd_main_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_main_tflops / PEAK_BF16_TFLOPS, 4),
+                     "avg_launch_ms": round(r["bwd_main_ms"], 4),
+                     "flops_per_launch": flops_bwd(bag), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        if bits is None:
+            from knap_inputs import make_qkv_dout
+            bits = make_qkv_dout(bag)
+        cb = cpu_baseline(bag, bits, args.cpu_budget)
+        log(f"[bench] cpu oracle: {cb['value'] * 1e3:.2f} GFLOP/s on {cb['cores']} threads ({cb['sample']})")
+        out["cpu_baseline"] = {**cb, "value": round(cb["value"], 6)}
+    print(json.dumps(out), flush=True)
+
+
+def run_fit(args):
+    """Cost-model experiment (Sec. 3.1 / Fig. 2 analogue): fit a, b of t = a sumL2 + b sumL on
+    single-sequence bags, then report the relative residual on the benchmark bags and random bags."""
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import BagSpec, config_bag
+
+    ev = HipEvents()
+    report = {"families": {}}
+    for fam, (H, d) in {"H24_d128": (24, 128), "H3_d128": (3, 128)}.items():
+        cal_L = [256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536] + ([131072] if H == 3 else [])
+        rows = []
+        for L in cal_L:
+            bag = BagSpec(f"cal{L}", [L], H=H, d=d, seed=1234 + L)
+            dev = device_inputs_fast(bag)
+            r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+            rows.append({"L": L, "ms": r["gpu_ms_per_step"],
+                         "tflops": 14.0 * H * d * L * L / (r["gpu_ms_per_step"] * 1e-3) / 1e12})
+            log(f"[fit] {fam} L={L}: {rows[-1]['ms']:.3f} ms, {rows[-1]['tflops']:.1f} TF/s")
+            del dev, r
+            torch.cuda.empty_cache()
+        s2 = [float(r["L"]) ** 2 for r in rows]
+        s1 = [float(r["L"]) for r in rows]
+        t = [r["ms"] for r in rows]
+        a, b, resid = K.knap_fit_cost_model(s2, s1, t)
+        evals = []
+        cfgs = [1, 2, 3] if H == 24 else [4]
+        for ci in cfgs:
+            for so in range(3 if ci != 4 else 1):
+                bag = config_bag(ci, seed_offset=so)
+                dev = device_inputs_fast(bag)
+                r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+                pred = a * bag.sum_l2 + b * bag.total_tokens
+                evals.append({"config": ci, "seed_offset": so, "T": bag.total_tokens, "sum_l2": bag.sum_l2,
+                              "ms": r["gpu_ms_per_step"], "pred_ms": pred,
+                              "rel_resid": abs(r["gpu_ms_per_step"] - pred) / r["gpu_ms_per_step"]})
+                log(f"[fit] {fam} cfg{ci}/{so}: measured {r['gpu_ms_per_step']:.3f} ms, model {pred:.3f} ms, "
+                    f"resid {evals[-1]['rel_resid'] * 100:.1f}%")
+                del dev, r
+                torch.cuda.empty_cache()
+        report["families"][fam] = {"a_ms_per_tok2": a, "b_ms_per_tok": b, "calibration_max_rel_resid": resid,
+                                   "calibration": rows, "evaluation": evals}
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    path = os.path.join(ROOT, "gpurun_out", "fit_report.json")
+    with open(path, "w") as f:
+        json.dump(report, f, indent=1)
+    log(f"[fit] wrote {path}")
+    print(json.dumps({"fit_report": path}), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4 (default 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
+    ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the step; --gpus must be 1 "
+              "(no collectives or multi-GPU path exist in this library).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    if args.fit:
+        run_fit(args)
+    else:
+        run_default(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -24,7 +24,7 @@ KNAP_MAX_SEQS = 2048
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it first with `python -m paper_2508_06001_amd.build` "
+        f"{LIB_PATH} is missing: build it first with `python paper_2508_06001_amd/build.py` "
         "(there is no CPU or PyTorch fallback for the attention path)")
 
 # PyTorch ships its own HIP runtime (same SONAME as the system one).  It must be
@@ -45,6 +45,7 @@ _SIGNATURES = {
     "knap_strerror": (C.c_char_p, [_i]),
     "knap_last_hip_error": (_i, []),
     "knap_launch_workgroups": (_i, [_i]),
+    "knap_bwd_profile_events": (None, [_vp, _vp]),
     "knap_seq_cost": (_d, [_i64, _d, _d]),
     "knap_flux_workload": (_d, [_i64, _i64, _d]),
     "knap_fit_cost_model": (_i, [_pd, _pd, _pd, _i, _pd, _pd, _pd]),
@@ -128,6 +129,11 @@ def knap_varlen_attn_bwd(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale:
 
 def knap_last_hip_error() -> int:
     return int(lib.knap_last_hip_error())
+
+
+def knap_bwd_profile_events(start: Optional[int], stop: Optional[int]) -> None:
+    """Raw hipEvent_t handles (ints) recorded around the main backward kernel; None switches it off."""
+    lib.knap_bwd_profile_events(start or 0, stop or 0)
 
 
 def knap_launch_workgroups(which: int) -> int:

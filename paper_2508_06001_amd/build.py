@@ -1,6 +1,6 @@
 """Builds libknapattn.so in-tree with hipcc for gfx950.
 
-    python -m paper_2508_06001_amd.build
+    python paper_2508_06001_amd/build.py
 
 The shared library is written next to this file.  Nothing is built at import
 time: the binding loads what this step produced and fails loudly otherwise.

@@ -8,6 +8,8 @@
 namespace {
 
 thread_local int g_last_hip_error = 0;
+thread_local hipEvent_t g_prof_start = nullptr;
+thread_local hipEvent_t g_prof_stop = nullptr;
 
 struct DeviceInfo {
   int cus = 0;
@@ -108,7 +110,7 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
   const int aux_grid = di->cus * 8;
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
                                         total_tokens, delta, dq_acc, grid, aux_grid,
-                                        static_cast<hipStream_t>(stream));
+                                        static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;
 }
@@ -127,6 +129,11 @@ const char* knap_strerror(int code) {
 }
 
 int knap_last_hip_error(void) { return g_last_hip_error; }
+
+void knap_bwd_profile_events(void* start, void* stop) {
+  g_prof_start = static_cast<hipEvent_t>(start);
+  g_prof_stop = static_cast<hipEvent_t>(stop);
+}
 
 int knap_launch_workgroups(int which) {
   DeviceInfo* di = device_info();

@@ -276,17 +276,20 @@ template <int D>
 static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H,
                                float scale, const void* out, const float* lse, const void* dout,
                                void* dq, void* dk, void* dv, int64_t T, float* delta, float* dq_acc,
-                               int grid, int aux_grid, hipStream_t stream) {
+                               int grid, int aux_grid, hipStream_t stream,
+                               hipEvent_t ev_start, hipEvent_t ev_stop) {
   hipLaunchKernelGGL(attn_bwd_prep_kernel<D>, dim3(aux_grid), dim3(kThreads), 0, stream,
                      (const __bf16*)out, (const __bf16*)dout, T, H, delta, dq_acc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
+  if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_kernel<D>, dim3(grid), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
                      (const float*)delta, cu, n_seq, H, scale, dq_acc, (__bf16*)dk, (__bf16*)dv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (ev_start && ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_convert_kernel, dim3(aux_grid), dim3(kThreads), 0, stream,
                      (const float*)dq_acc, T * H * D / 8, scale, (__bf16*)dq);
   return hipGetLastError();
@@ -295,12 +298,12 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
                       void* dq, void* dk, void* dv, int64_t T, float* delta, float* dq_acc,
-                      int grid, int aux_grid, hipStream_t stream) {
+                      int grid, int aux_grid, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (d == 64)
     return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, dq_acc,
-                            grid, aux_grid, stream);
+                            grid, aux_grid, stream, ev_start, ev_stop);
   return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, dq_acc,
-                           grid, aux_grid, stream);
+                           grid, aux_grid, stream, ev_start, ev_stop);
 }
 
 int bwd_workgroups_per_cu(int d) {

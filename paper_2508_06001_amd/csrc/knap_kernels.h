@@ -12,7 +12,8 @@ hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
                       void* dq, void* dk, void* dv, int64_t T, float* delta, float* dq_acc,
-                      int grid, int aux_grid, hipStream_t stream);
+                      int grid, int aux_grid, hipStream_t stream,
+                      hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // resident workgroups per compute unit of the persistent kernels
 int fwd_workgroups_per_cu(int d);
