@@ -89,15 +89,15 @@ const char* knap_strerror(int code);
 int knap_last_hip_error(void);
 
 /* Benchmark hook.  While both are non-NULL, every backward call made by this
- * thread records `start` right before and `stop` right after its main kernel
- * (the kv-tile-major recompute kernel) on the call's stream; the preprocess and
- * dq-convert kernels stay outside the pair.  hipEvent_t passed as void*, owned
+ * thread records `start` right before and `stop` right after its dK/dV kernel
+ * (the longest kernel of the path) on the call's stream; the preprocess and dQ
+ * kernels stay outside the pair.  hipEvent_t passed as void*, owned
  * by the caller.  Pass NULLs to switch it off.  Not for use under graph capture. */
 void knap_bwd_profile_events(void* start, void* stop);
 
 /* Number of persistent workgroups the forward / backward kernels are launched
  * with on the current device (for benchmarks and tests; <= 0 on error). */
-int knap_launch_workgroups(int which /* 0 = forward, 1 = backward */);
+int knap_launch_workgroups(int which /* 0 = forward, 1 = backward dK/dV, 2 = backward dQ */);
 
 /* ------------------------------------------------------------------------
  * Host-side workload model and balancer (pure C, host pointers, no GPU).

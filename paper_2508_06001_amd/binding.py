@@ -11,7 +11,8 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libknapattn.so")
+# KNAPATTN_LIB selects another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("KNAPATTN_LIB") or os.path.join(_HERE, "libknapattn.so")
 
 KNAP_OK = 0
 KNAP_ERR_INVALID_ARG = -1

@@ -34,16 +34,16 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH, obj_subdir: str = "_build") -> str:
     hipcc = _hipcc()
-    obj_dir = os.path.join(HERE, "_build")
+    obj_dir = os.path.join(HERE, obj_subdir)
     os.makedirs(obj_dir, exist_ok=True)
     inc = ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
     objs = []
     procs = []
     for src in HIP_SOURCES:
         obj = os.path.join(obj_dir, src + ".o")
-        cmd = [hipcc] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + HIP_FLAGS + list(extra_flags) + inc + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src in C_SOURCES:
@@ -58,11 +58,11 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError("build failed: %s\n%s" % (" ".join(cmd), out))
         if verbose and out.strip():
             print(out)
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs + ["-lm"]
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out_path] + objs + ["-lm"]
     r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed: %s\n%s" % (" ".join(link), r.stdout))
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -14,7 +14,8 @@ thread_local hipEvent_t g_prof_stop = nullptr;
 struct DeviceInfo {
   int cus = 0;
   int fwd_wg[2] = {0, 0};   // workgroups per CU, index 0: d = 64, 1: d = 128
-  int bwd_wg[2] = {0, 0};
+  int dkdv_wg[2] = {0, 0};
+  int dq_wg[2] = {0, 0};
 };
 
 // per-device launch geometry, filled on first use (occupancy queries do not allocate)
@@ -31,8 +32,10 @@ DeviceInfo* device_info() {
     }
     di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
     di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
-    di.bwd_wg[0] = knap::bwd_workgroups_per_cu(64);
-    di.bwd_wg[1] = knap::bwd_workgroups_per_cu(128);
+    di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64);
+    di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
+    di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
+    di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
     di.cus = cus;
   }
   return &di;
@@ -76,9 +79,7 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d) {
   (void)n_seq;
   if (total_tokens <= 0 || H <= 0 || d <= 0) return 0;
-  const size_t delta = round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256);
-  const size_t dq_acc = round_up(static_cast<size_t>(total_tokens) * H * d * sizeof(float), 256);
-  return delta + dq_acc;
+  return round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256);   // delta, fp32 (H, T)
 }
 
 int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
@@ -104,12 +105,11 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
 
   float* delta = static_cast<float*>(workspace);
-  float* dq_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) +
-                                           round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256));
-  const int grid = di->cus * di->bwd_wg[d == 128];
+  const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
+  const int grid_dq = di->cus * di->dq_wg[d == 128];
   const int aux_grid = di->cus * 8;
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
-                                        total_tokens, delta, dq_acc, grid, aux_grid,
+                                        total_tokens, delta, grid_dkdv, grid_dq, aux_grid,
                                         static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;
@@ -138,7 +138,7 @@ void knap_bwd_profile_events(void* start, void* stop) {
 int knap_launch_workgroups(int which) {
   DeviceInfo* di = device_info();
   if (!di) return -1;
-  return di->cus * (which == 0 ? di->fwd_wg[1] : di->bwd_wg[1]);
+  return di->cus * (which == 0 ? di->fwd_wg[1] : which == 1 ? di->dkdv_wg[1] : di->dq_wg[1]);
 }
 
 }  // extern "C"

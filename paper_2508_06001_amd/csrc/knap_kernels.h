@@ -11,12 +11,13 @@ hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, int64_t T, float* delta, float* dq_acc,
-                      int grid, int aux_grid, hipStream_t stream,
+                      void* dq, void* dk, void* dv, int64_t T, float* delta,
+                      int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // resident workgroups per compute unit of the persistent kernels
 int fwd_workgroups_per_cu(int d);
-int bwd_workgroups_per_cu(int d);
+int bwd_dkdv_workgroups_per_cu(int d);
+int bwd_dq_workgroups_per_cu(int d);
 
 }  // namespace knap

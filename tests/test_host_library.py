@@ -39,7 +39,7 @@ def test_attention_entry_points_reject_bad_arguments_without_touching_a_gpu():
     assert g(256, 512, 768, 1024, 1, 2, 64, 0.125, 1280, 1536, 1792, 2048, 2304, 2560, 100, 0, 0, 0) \
         == K.KNAP_ERR_INVALID_ARG          # no workspace
     need = K.knap_varlen_attn_bwd_workspace_bytes(100, 1, 2, 64)
-    assert need >= 100 * 2 * 4 + 100 * 2 * 64 * 4
+    assert need >= 100 * 2 * 4
     assert g(256, 512, 768, 1024, 1, 2, 64, 0.125, 1280, 1536, 1792, 2048, 2304, 2560, 100, 4096, need - 1, 0) \
         == K.KNAP_ERR_WORKSPACE_TOO_SMALL
     assert K.knap_strerror(K.KNAP_ERR_WORKSPACE_TOO_SMALL) == "workspace too small"
