@@ -30,6 +30,13 @@
 #include "knap_device.h"
 #include "knap_kernels.h"
 
+// Scheduling fence: keeps a batch of LDS reads ahead of the MFMA group that follows it.
+#if defined(KNAP_NO_SCHED_FENCE)
+#define KNAP_SCHED_FENCE() ((void)0)
+#else
+#define KNAP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
 namespace knap {
 
 template <int D>
@@ -79,10 +86,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
   int* s_order = s_dyn;
   int* s_start = s_dyn + n_seq;
   __shared__ int s_part[kThreads];
-  __shared__ __attribute__((aligned(16))) __bf16 sQ[C::BM * C::QS];
-  __shared__ __attribute__((aligned(16))) __bf16 sdO[C::BM * C::QS];
-  __shared__ __attribute__((aligned(16))) float sLse[C::BM];     // LSE in base 2; +inf for rows past the end
-  __shared__ __attribute__((aligned(16))) float sDelta[C::BM];
+  // two copies of the query-side tiles: the next step's tile lands while this one is used
+  __shared__ __attribute__((aligned(16))) __bf16 sQ[2][C::BM * C::QS];
+  __shared__ __attribute__((aligned(16))) __bf16 sdO[2][C::BM * C::QS];
+  __shared__ __attribute__((aligned(16))) float sLse[2][C::BM];     // LSE in base 2; +inf for rows past the end
+  __shared__ __attribute__((aligned(16))) float sDelta[2][C::BM];
 
   const int n_items = build_schedule<C::BN>(cu, n_seq, H, s_order, s_start, s_part);
   const int T = cu[n_seq];
@@ -93,9 +101,11 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
   const size_t row_stride = (size_t)H * D;
+  const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
 
   constexpr int TPR = D / 8;
   constexpr int RPP = kThreads / TPR;
+  constexpr int NP = C::BM / RPP;            // 16-byte loads per thread and tensor per tile
   const int ld_row = tid / TPR;
   const int ld_col = (tid % TPR) * 8;
 
@@ -106,97 +116,130 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
     const size_t head_off = (size_t)it.head * D;
     const __bf16* q_base = q + (size_t)it.row0 * row_stride + head_off;
     const __bf16* do_base = dout + (size_t)it.row0 * row_stride + head_off;
-    const __bf16* k_base = k + (size_t)it.row0 * row_stride + head_off;
-    const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
     const float* lse_base = lse + (size_t)it.head * T + it.row0;
     const float* delta_base = delta + (size_t)it.head * T + it.row0;
 
-    // this wave's key rows as B operands of S = Q K^T and dP = dO V^T
-    const int kv_row = kv0 + 32 * wave + l32;
-    const bool kv_valid = kv_row < L;
+    // this wave's key rows as B operands of S = Q K^T and dP = dO V^T (rows past the end read as zero)
     bf16x8 kf[C::KC], vf[C::KC];
+    {
+      const uint32_t kv_bytes = (uint32_t)min(L - kv0, C::BN) * row_bytes;
+      const auto rk = make_rsrc(k + (size_t)(it.row0 + kv0) * row_stride + head_off, kv_bytes);
+      const auto rv = make_rsrc(v + (size_t)(it.row0 + kv0) * row_stride + head_off, kv_bytes);
+      const uint32_t off = (uint32_t)(32 * wave + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
 #pragma unroll
-    for (int cc = 0; cc < C::KC; ++cc) {
-      kf[cc] = kv_valid ? *reinterpret_cast<const bf16x8*>(k_base + (size_t)kv_row * row_stride + 16 * cc + 8 * hh)
-                        : zero_bf16x8();
-      vf[cc] = kv_valid ? *reinterpret_cast<const bf16x8*>(v_base + (size_t)kv_row * row_stride + 16 * cc + 8 * hh)
-                        : zero_bf16x8();
+      for (int cc = 0; cc < C::KC; ++cc) {
+        kf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rk, off + 32u * cc));
+        vf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rv, off + 32u * cc));
+      }
     }
 
     f32x16 dk_acc[C::NB], dv_acc[C::NB];
 #pragma unroll
     for (int nb = 0; nb < C::NB; ++nb) { dk_acc[nb] = zero16(); dv_acc[nb] = zero16(); }
 
-    for (int q0 = 0; q0 < L; q0 += C::BM) {
-      __syncthreads();   // the previous step's tiles are no longer being read
+    const int n_tiles = (L + C::BM - 1) / C::BM;
+    u32x4 gq[NP], gd[NP];
+    float g_lse = 0.f, g_delta = 0.f;
+
+    auto fetch_tile = [&](int t) {     // global -> registers
+      const int q0 = t * C::BM;
+      const uint32_t bytes = (uint32_t)min(L - q0, C::BM) * row_bytes;
+      const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, bytes);
+      const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, bytes);
 #pragma unroll
-      for (int p = 0; p < C::BM / RPP; ++p) {
-        const int r = p * RPP + ld_row;
-        u32x4 qq = {0u, 0u, 0u, 0u}, dd = {0u, 0u, 0u, 0u};
-        if (q0 + r < L) {
-          const size_t g = (size_t)(q0 + r) * row_stride + ld_col;
-          qq = *reinterpret_cast<const u32x4*>(q_base + g);
-          dd = *reinterpret_cast<const u32x4*>(do_base + g);
-        }
-        *reinterpret_cast<u32x4*>(&sQ[r * C::QS + ld_col]) = qq;
-        *reinterpret_cast<u32x4*>(&sdO[r * C::QS + ld_col]) = dd;
+      for (int p = 0; p < NP; ++p) {
+        const uint32_t off = (uint32_t)(p * RPP + ld_row) * row_bytes + (uint32_t)ld_col * 2u;
+        gq[p] = buffer_load16(rq, off);
+        gd[p] = buffer_load16(rd, off);
       }
       if (tid < C::BM) {
         const bool ok = q0 + tid < L;
-        sLse[tid] = ok ? lse_base[q0 + tid] * kLog2e : INFINITY;   // +inf makes P = 0 on rows past the end
-        sDelta[tid] = ok ? delta_base[q0 + tid] : 0.f;
+        const int qi = ok ? q0 + tid : 0;
+        const float a = lse_base[qi], b = delta_base[qi];
+        g_lse = ok ? a * kLog2e : INFINITY;     // +inf makes P = 0 on rows past the end
+        g_delta = ok ? b : 0.f;
       }
-      __syncthreads();
+    };
+    auto commit_tile = [&](int buf) {  // registers -> LDS
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const int r = p * RPP + ld_row;
+        *reinterpret_cast<u32x4*>(&sQ[buf][r * C::QS + ld_col]) = gq[p];
+        *reinterpret_cast<u32x4*>(&sdO[buf][r * C::QS + ld_col]) = gd[p];
+      }
+      if (tid < C::BM) { sLse[buf][tid] = g_lse; sDelta[buf][tid] = g_delta; }
+    };
 
-      // S and dP: (64 queries) x (this wave's 32 keys)
-      f32x16 s[C::MB], dp[C::MB];
+    __syncthreads();       // the previous item is done with both buffers
+    fetch_tile(0);
+    commit_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+      const int cur = t & 1;
+      const bool more = t + 1 < n_tiles;
+      if (more) fetch_tile(t + 1);
+      const __bf16* tQ = sQ[cur];
+      const __bf16* tdO = sdO[cur];
+
 #pragma unroll
       for (int mb = 0; mb < C::MB; ++mb) {
-        s[mb] = zero16();
-        dp[mb] = zero16();
+        // S and dP for 32 queries x this wave's 32 keys; all row fragments are requested first
+        bf16x8 aq[C::KC], ad[C::KC];
 #pragma unroll
         for (int cc = 0; cc < C::KC; ++cc) {
           const int off = (32 * mb + l32) * C::QS + 16 * cc + 8 * hh;
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&sQ[off]);
-          const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&sdO[off]);
-          s[mb] = mfma32(aq, kf[cc], s[mb]);
-          dp[mb] = mfma32(ad, vf[cc], dp[mb]);
+          aq[cc] = *reinterpret_cast<const bf16x8*>(&tQ[off]);
+          ad[cc] = *reinterpret_cast<const bf16x8*>(&tdO[off]);
         }
-      }
-
-      // P = exp2(c S - LSE2), dS = P (dP - delta); register r is query 32 mb + 8 (r / 4) + 4 hh + r % 4
+        KNAP_SCHED_FENCE();
+        f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb)
+        for (int cc = 0; cc < C::KC; ++cc) {
+          s = mfma32(aq[cc], kf[cc], s);
+          dp = mfma32(ad[cc], vf[cc], dp);
+        }
+        // transposed dO and Q operands for the second pair of products, requested before the softmax math
+        bf16x8 bo[2][C::NB], bq[2][C::NB];
+#pragma unroll
+        for (int cq = 0; cq < 2; ++cq)
+#pragma unroll
+          for (int nb = 0; nb < C::NB; ++nb) {
+            const int k_lo = 32 * mb + 16 * cq + 4 * hh;
+            bo[cq][nb] = lds_operand_tr(tdO, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
+            bq[cq][nb] = lds_operand_tr(tQ, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
+          }
+        KNAP_SCHED_FENCE();
+        // P = exp2(c S - LSE2), dS = P (dP - delta); register r is query 32 mb + 8 (r / 4) + 4 hh + r % 4
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int qi = 32 * mb + 8 * g + 4 * hh;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[qi]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDelta[qi]);
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[cur][qi]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDelta[cur][qi]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(__builtin_fmaf(s[mb][4 * g + e], c, -l4[e]));
-            s[mb][4 * g + e] = p;
-            dp[mb][4 * g + e] = p * (dp[mb][4 * g + e] - d4[e]);
+            const float p = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
+            s[4 * g + e] = p;
+            dp[4 * g + e] = p * (dp[4 * g + e] - d4[e]);
           }
         }
-
-      // dV += P^T dO and dK += dS^T Q: contraction over queries in chunks of 16;
-      // element e of chunk cq is query 16 cq + 8 (e / 4) + 4 hh + e % 4 on both sides
+        // dV += P^T dO and dK += dS^T Q; element e of chunk cq is query 32 mb + 16 cq + 8 (e / 4) + 4 hh + e % 4
 #pragma unroll
-      for (int cq = 0; cq < C::BM / 16; ++cq) {
-        const int mb = cq >> 1, r0 = 8 * (cq & 1);
-        const bf16x8 pa = pack8(s[mb][r0], s[mb][r0 + 1], s[mb][r0 + 2], s[mb][r0 + 3],
-                                s[mb][r0 + 4], s[mb][r0 + 5], s[mb][r0 + 6], s[mb][r0 + 7]);
-        const bf16x8 da = pack8(dp[mb][r0], dp[mb][r0 + 1], dp[mb][r0 + 2], dp[mb][r0 + 3],
-                                dp[mb][r0 + 4], dp[mb][r0 + 5], dp[mb][r0 + 6], dp[mb][r0 + 7]);
+        for (int cq = 0; cq < 2; ++cq) {
+          const int r0 = 8 * cq;
+          const bf16x8 pa = pack8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
+          const bf16x8 da = pack8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3],
+                                  dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
 #pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-          const bf16x8 bo = lds_operand_tr(sdO, C::QS, 16 * cq + 4 * hh, 16 * cq + 8 + 4 * hh, 32 * nb, lane);
-          const bf16x8 bq = lds_operand_tr(sQ, C::QS, 16 * cq + 4 * hh, 16 * cq + 8 + 4 * hh, 32 * nb, lane);
-          dv_acc[nb] = mfma32(pa, bo, dv_acc[nb]);
-          dk_acc[nb] = mfma32(da, bq, dk_acc[nb]);
+          for (int nb = 0; nb < C::NB; ++nb) {
+            dv_acc[nb] = mfma32(pa, bo[cq][nb], dv_acc[nb]);
+            dk_acc[nb] = mfma32(da, bq[cq][nb], dk_acc[nb]);
+          }
         }
       }
+
+      if (more) commit_tile(cur ^ 1);
+      __syncthreads();     // next tile visible; this tile no longer read
     }
 
     // dK (scaled) and dV rows of this wave: register r is key 8 (r / 4) + 4 hh + r % 4, lane is d

@@ -73,6 +73,18 @@ __device__ __forceinline__ bf16x8 lds_operand_tr(const __bf16* X, int ld, int k_
   return join(lo, hi);
 }
 
+// Bounds-checked global loads.  A raw buffer descriptor covers `bytes` bytes from
+// `base`; a 16-byte load at an offset at or past `bytes` returns zeros instead of
+// touching memory, which replaces per-row predication (and its branches) when a
+// tile hangs over the end of a sequence.  base and bytes must be wave-uniform.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 0);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float xor32(float x) {
