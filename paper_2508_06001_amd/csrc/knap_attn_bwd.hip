@@ -36,6 +36,17 @@
 #else
 #define KNAP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #endif
+// Interleave hints: the scheduler fills groups of the given instruction class in
+// the order the hints appear, inside one fenced region.
+#if defined(KNAP_NO_SCHED_GROUPS)
+#define KNAP_SGB(mask, n) ((void)0)
+#else
+#define KNAP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#endif
+#define KNAP_SG_VALU 0x002
+#define KNAP_SG_MFMA 0x008
+#define KNAP_SG_DS_READ 0x100
+#define KNAP_SG_DS_WRITE 0x200
 
 namespace knap {
 
@@ -141,9 +152,10 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
     u32x4 gq[NP], gd[NP];
     float g_lse = 0.f, g_delta = 0.f;
 
-    auto fetch_tile = [&](int t) {     // global -> registers
+    // global -> registers; a tile past the end of the sequence reads as zeros (LSE +inf)
+    auto fetch_tile = [&](int t) {
       const int q0 = t * C::BM;
-      const uint32_t bytes = (uint32_t)min(L - q0, C::BM) * row_bytes;
+      const uint32_t bytes = (uint32_t)max(0, min(L - q0, C::BM)) * row_bytes;
       const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, bytes);
       const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, bytes);
 #pragma unroll
@@ -152,22 +164,22 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
         gq[p] = buffer_load16(rq, off);
         gd[p] = buffer_load16(rd, off);
       }
-      if (tid < C::BM) {
-        const bool ok = q0 + tid < L;
-        const int qi = ok ? q0 + tid : 0;
-        const float a = lse_base[qi], b = delta_base[qi];
-        g_lse = ok ? a * kLog2e : INFINITY;     // +inf makes P = 0 on rows past the end
-        g_delta = ok ? b : 0.f;
-      }
+      const int r = tid & (C::BM - 1);          // every row is fetched by kThreads / BM threads
+      const bool ok = q0 + r < L;
+      const int qi = ok ? q0 + r : 0;
+      const float a = lse_base[qi], b = delta_base[qi];
+      g_lse = ok ? a * kLog2e : INFINITY;       // +inf makes P = 0 on rows past the end
+      g_delta = ok ? b : 0.f;
     };
-    auto commit_tile = [&](int buf) {  // registers -> LDS
+    auto commit_tile = [&](int buf) {           // registers -> LDS
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         const int r = p * RPP + ld_row;
         *reinterpret_cast<u32x4*>(&sQ[buf][r * C::QS + ld_col]) = gq[p];
         *reinterpret_cast<u32x4*>(&sdO[buf][r * C::QS + ld_col]) = gd[p];
       }
-      if (tid < C::BM) { sLse[buf][tid] = g_lse; sDelta[buf][tid] = g_delta; }
+      sLse[buf][tid & (C::BM - 1)] = g_lse;
+      sDelta[buf][tid & (C::BM - 1)] = g_delta;
     };
 
     __syncthreads();       // the previous item is done with both buffers
@@ -177,30 +189,29 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
 
     for (int t = 0; t < n_tiles; ++t) {
       const int cur = t & 1;
-      const bool more = t + 1 < n_tiles;
-      if (more) fetch_tile(t + 1);
+      fetch_tile(t + 1);
       const __bf16* tQ = sQ[cur];
       const __bf16* tdO = sdO[cur];
+      const float* tLse = sLse[cur];
+      const float* tDelta = sDelta[cur];
 
-#pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb) {
-        // S and dP for 32 queries x this wave's 32 keys; all row fragments are requested first
-        bf16x8 aq[C::KC], ad[C::KC];
+      // The 64-query tile is processed as two halves of 32 queries.  With one wave per SIMD
+      // nothing overlaps unless it is interleaved in program order, so the halves form a
+      // static software pipeline of four slots; in each slot one MFMA group runs against
+      // the LDS reads or the softmax arithmetic of the other half:
+      //   slot 1: S, dP of half 0          | row fragments of half 1
+      //   slot 2: S, dP of half 1          | P, dS of half 0, transposed fragments of half 0
+      //   slot 3: dV, dK += half 0         | P, dS of half 1, transposed fragments of half 1
+      //   slot 4: dV, dK += half 1         | next tile: registers -> LDS
+      auto read_rows = [&](int mb, bf16x8 (&aq)[C::KC], bf16x8 (&ad)[C::KC]) {
 #pragma unroll
         for (int cc = 0; cc < C::KC; ++cc) {
           const int off = (32 * mb + l32) * C::QS + 16 * cc + 8 * hh;
           aq[cc] = *reinterpret_cast<const bf16x8*>(&tQ[off]);
           ad[cc] = *reinterpret_cast<const bf16x8*>(&tdO[off]);
         }
-        KNAP_SCHED_FENCE();
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) {
-          s = mfma32(aq[cc], kf[cc], s);
-          dp = mfma32(ad[cc], vf[cc], dp);
-        }
-        // transposed dO and Q operands for the second pair of products, requested before the softmax math
-        bf16x8 bo[2][C::NB], bq[2][C::NB];
+      };
+      auto read_transposed = [&](int mb, bf16x8 (&bo)[2][C::NB], bf16x8 (&bq)[2][C::NB]) {
 #pragma unroll
         for (int cq = 0; cq < 2; ++cq)
 #pragma unroll
@@ -209,36 +220,84 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
             bo[cq][nb] = lds_operand_tr(tdO, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
             bq[cq][nb] = lds_operand_tr(tQ, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
           }
-        KNAP_SCHED_FENCE();
-        // P = exp2(c S - LSE2), dS = P (dP - delta); register r is query 32 mb + 8 (r / 4) + 4 hh + r % 4
+      };
+      auto scores = [&](const bf16x8 (&aq)[C::KC], const bf16x8 (&ad)[C::KC], f32x16& s, f32x16& dp) {
+        s = zero16();
+        dp = zero16();
+#pragma unroll
+        for (int cc = 0; cc < C::KC; ++cc) {
+          s = mfma32(aq[cc], kf[cc], s);
+          dp = mfma32(ad[cc], vf[cc], dp);
+        }
+      };
+      // P = exp2(c S - LSE2), dS = P (dP - delta); register r is query 32 mb + 8 (r / 4) + 4 hh + r % 4.
+      // Packed so that element e of chunk cq is query 32 mb + 16 cq + 8 (e / 4) + 4 hh + e % 4.
+      auto softmax_math = [&](int mb, const f32x16& s, const f32x16& dp, bf16x8 (&pa)[2], bf16x8 (&da)[2]) {
+        float p[16], ds[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int qi = 32 * mb + 8 * g + 4 * hh;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[cur][qi]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDelta[cur][qi]);
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&tLse[qi]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&tDelta[qi]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
-            s[4 * g + e] = p;
-            dp[4 * g + e] = p * (dp[4 * g + e] - d4[e]);
+            p[4 * g + e] = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
+            ds[4 * g + e] = p[4 * g + e] * (dp[4 * g + e] - d4[e]);
           }
         }
-        // dV += P^T dO and dK += dS^T Q; element e of chunk cq is query 32 mb + 16 cq + 8 (e / 4) + 4 hh + e % 4
 #pragma unroll
         for (int cq = 0; cq < 2; ++cq) {
           const int r0 = 8 * cq;
-          const bf16x8 pa = pack8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
-          const bf16x8 da = pack8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3],
-                                  dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
+          pa[cq] = pack8(p[r0], p[r0 + 1], p[r0 + 2], p[r0 + 3], p[r0 + 4], p[r0 + 5], p[r0 + 6], p[r0 + 7]);
+          da[cq] = pack8(ds[r0], ds[r0 + 1], ds[r0 + 2], ds[r0 + 3], ds[r0 + 4], ds[r0 + 5], ds[r0 + 6], ds[r0 + 7]);
+        }
+      };
+      auto accumulate = [&](const bf16x8 (&pa)[2], const bf16x8 (&da)[2],
+                            const bf16x8 (&bo)[2][C::NB], const bf16x8 (&bq)[2][C::NB]) {
+#pragma unroll
+        for (int cq = 0; cq < 2; ++cq)
 #pragma unroll
           for (int nb = 0; nb < C::NB; ++nb) {
-            dv_acc[nb] = mfma32(pa, bo[cq][nb], dv_acc[nb]);
-            dk_acc[nb] = mfma32(da, bq[cq][nb], dk_acc[nb]);
+            dv_acc[nb] = mfma32(pa[cq], bo[cq][nb], dv_acc[nb]);
+            dk_acc[nb] = mfma32(da[cq], bq[cq][nb], dk_acc[nb]);
           }
-        }
-      }
+      };
+      constexpr int NM_A = 2 * C::KC;        // MFMAs of one S, dP group
+      constexpr int NM_C = 4 * C::NB;        // MFMAs of one dV, dK group
 
-      if (more) commit_tile(cur ^ 1);
+      bf16x8 aq0[C::KC], ad0[C::KC], aq1[C::KC], ad1[C::KC];
+      bf16x8 bo0[2][C::NB], bq0[2][C::NB], bo1[2][C::NB], bq1[2][C::NB];
+      bf16x8 pa0[2], da0[2], pa1[2], da1[2];
+      f32x16 s0, dp0, s1, dp1;
+
+      read_rows(0, aq0, ad0);
+      KNAP_SCHED_FENCE();
+      // slot 1
+      scores(aq0, ad0, s0, dp0);
+      read_rows(1, aq1, ad1);
+#pragma unroll
+      for (int i = 0; i < NM_A; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); }
+      KNAP_SCHED_FENCE();
+      // slot 2
+      scores(aq1, ad1, s1, dp1);
+      softmax_math(0, s0, dp0, pa0, da0);
+      read_transposed(0, bo0, bq0);
+#pragma unroll
+      for (int i = 0; i < NM_A; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 3); KNAP_SGB(KNAP_SG_VALU, 7); }
+      KNAP_SCHED_FENCE();
+      // slot 3
+      accumulate(pa0, da0, bo0, bq0);
+      softmax_math(1, s1, dp1, pa1, da1);
+      read_transposed(1, bo1, bq1);
+#pragma unroll
+      for (int i = 0; i < NM_C; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 3); KNAP_SGB(KNAP_SG_VALU, 7); }
+      KNAP_SCHED_FENCE();
+      // slot 4
+      accumulate(pa1, da1, bo1, bq1);
+      commit_tile(cur ^ 1);
+#pragma unroll
+      for (int i = 0; i < NM_C; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_WRITE, 1); }
+      KNAP_SCHED_FENCE();
       __syncthreads();     // next tile visible; this tile no longer read
     }
 

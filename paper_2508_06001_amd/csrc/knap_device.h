@@ -78,7 +78,12 @@ __device__ __forceinline__ bf16x8 lds_operand_tr(const __bf16* X, int ld, int k_
 // touching memory, which replaces per-row predication (and its branches) when a
 // tile hangs over the end of a sequence.  base and bytes must be wave-uniform.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+  // readfirstlane pins the descriptor to scalar registers (no per-lane descriptor loop)
+  const uint64_t b = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  void* p = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(p, 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
 }
 
 __device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
@@ -177,12 +182,15 @@ __device__ __forceinline__ WorkItem decode_item(int w, const int32_t* __restrict
     const int mid = (lo + hi + 1) >> 1;
     if (s_start[mid] <= w) lo = mid; else hi = mid - 1;
   }
-  const int s = s_order[lo];
+  // every lane computed the same values; say so, so that addresses and buffer
+  // descriptors derived from the item live in scalar registers
+  const int s = __builtin_amdgcn_readfirstlane(s_order[lo]);
+  const int first = __builtin_amdgcn_readfirstlane(s_start[lo]);
   WorkItem it;
-  it.row0 = cu[s];
-  it.len = cu[s + 1] - it.row0;
+  it.row0 = __builtin_amdgcn_readfirstlane(cu[s]);
+  it.len = __builtin_amdgcn_readfirstlane(cu[s + 1]) - it.row0;
   const int tiles = (it.len + TILE - 1) / TILE;
-  const int rem = w - s_start[lo];
+  const int rem = w - first;
   it.head = rem / tiles;
   it.tile = rem - it.head * tiles;
   return it;
