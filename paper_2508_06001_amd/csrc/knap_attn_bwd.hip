@@ -30,24 +30,6 @@
 #include "knap_device.h"
 #include "knap_kernels.h"
 
-// Scheduling fence: keeps a batch of LDS reads ahead of the MFMA group that follows it.
-#if defined(KNAP_NO_SCHED_FENCE)
-#define KNAP_SCHED_FENCE() ((void)0)
-#else
-#define KNAP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
-// Interleave hints: the scheduler fills groups of the given instruction class in
-// the order the hints appear, inside one fenced region.
-#if defined(KNAP_NO_SCHED_GROUPS)
-#define KNAP_SGB(mask, n) ((void)0)
-#else
-#define KNAP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#endif
-#define KNAP_SG_VALU 0x002
-#define KNAP_SG_MFMA 0x008
-#define KNAP_SG_DS_READ 0x100
-#define KNAP_SG_DS_WRITE 0x200
-
 namespace knap {
 
 template <int D>

@@ -4,7 +4,9 @@
 //
 // One persistent workgroup (4 waves) takes work items (sequence, head, 128-row
 // query tile) from the longest-first schedule.  Wave w owns 32 query rows and
-// streams the sequence's keys and values through LDS in tiles of 64 rows.
+// streams the sequence's keys and values through LDS in tiles of 64 rows; the
+// next tile travels global -> registers while the current one is used, and is
+// written to the other LDS buffer behind one barrier per tile.
 //
 // Orientation: the scores are computed transposed, S^T = K Q^T, so that in the
 // MFMA result layout a lane holds ONE query (column l % 32) and its registers
@@ -12,8 +14,16 @@
 // exchange between lanes l and l ^ 32, the rescale factor is a per-lane scalar,
 // and P^T in that layout is, unchanged, the B operand of O^T += V^T P^T.  V^T
 // fragments come from the row-major V tile through transposing LDS reads.
+//
+// Softmax bookkeeping: the exponent reference m_ref of a query only moves when
+// a tile's maximum exceeds it by more than 2^8 in base-2 units (the first tile
+// always does).  Otherwise P is formed against the old reference, so P <= 256
+// and the accumulated output needs no rescaling; the final division by the row
+// sum removes the reference exactly as in the textbook recurrence.
 #include "knap_device.h"
 #include "knap_kernels.h"
+
+#include <type_traits>
 
 namespace knap {
 
@@ -21,11 +31,12 @@ template <int D>
 struct FwdCfg {
   static constexpr int BM = 128;         // query rows per work item
   static constexpr int BN = 64;          // key/value rows per LDS tile
-  static constexpr int KS = D + 8;       // K tile row stride (elements): +16 B keeps 128-bit row reads conflict-free
-  static constexpr int VS = D + 32;      // V tile row stride: +64 B spreads the 4-row transposing reads over all banks
   static constexpr int KC = D / 16;      // contraction chunks over d
   static constexpr int DB = D / 32;      // 32-wide blocks of d
+  static constexpr int TILE_ELEMS = BN * Tile<D>::LD;
 };
+
+constexpr float kRescaleThreshold = 8.0f;   // base-2 units
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
@@ -33,14 +44,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     const int32_t* __restrict__ cu, int n_seq, int H, float scale,
     __bf16* __restrict__ out, float* __restrict__ lse) {
   using C = FwdCfg<D>;
+  using TL = Tile<D>;
   extern __shared__ int s_dyn[];
   int* s_order = s_dyn;
   int* s_start = s_dyn + n_seq;
-  __shared__ int s_part[kThreads];
-  __shared__ __attribute__((aligned(16))) __bf16 sK[C::BN * C::KS];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[C::BN * C::VS];
+  __shared__ __attribute__((aligned(16))) __bf16 sK[2][C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 sV[2][C::TILE_ELEMS];
+  static_assert(sizeof(__bf16) * C::TILE_ELEMS >= sizeof(int) * kThreads, "scan scratch must fit in a tile");
 
-  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, s_part);
+  // the scan scratch of the schedule lives in the first K buffer, which is not in use yet
+  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK[0][0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -49,118 +62,192 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
   const size_t row_stride = (size_t)H * D;
+  const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
 
-  // global -> LDS tile copy geometry: 16 B per thread
-  constexpr int TPR = D / 8;                 // threads per row
+  // global -> LDS tile copy geometry: 16 B per thread and pass
+  constexpr int TPR = D / 8;                 // threads (16-byte chunks) per row
   constexpr int RPP = kThreads / TPR;        // rows per pass
+  constexpr int NP = C::BN / RPP;            // passes per tile
   const int ld_row = tid / TPR;
-  const int ld_col = (tid % TPR) * 8;
+  const int ld_chunk = tid % TPR;
 
   for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
-    const int q_row = it.tile * C::BM + wave * 32 + l32;      // row inside the sequence
+    const int q0 = it.tile * C::BM;
+    const int q_row = q0 + wave * 32 + l32;      // row inside the sequence
     const bool q_valid = q_row < L;
-    const __bf16* q_ptr = q + (size_t)(it.row0 + q_row) * row_stride + (size_t)it.head * D;
+    const size_t head_off = (size_t)it.head * D;
 
+    // this lane's query row as the B operand of S^T = K Q^T (rows past the end read as zero)
     bf16x8 qf[C::KC];
+    {
+      const auto rq = make_rsrc(q + (size_t)(it.row0 + q0) * row_stride + head_off,
+                                (uint32_t)min(L - q0, C::BM) * row_bytes);
+      const uint32_t off = (uint32_t)(wave * 32 + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
 #pragma unroll
-    for (int cc = 0; cc < C::KC; ++cc)
-      qf[cc] = q_valid ? *reinterpret_cast<const bf16x8*>(q_ptr + 16 * cc + 8 * hh) : zero_bf16x8();
+      for (int cc = 0; cc < C::KC; ++cc) qf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rq, off + 32u * cc));
+    }
 
     f32x16 o[C::DB];
 #pragma unroll
     for (int db = 0; db < C::DB; ++db) o[db] = zero16();
-    float m_run = -INFINITY;   // running max of the raw scores
-    float l_run = 0.f;         // this lane's share of the running sum (its 32 of the 64 keys per tile)
+    float m_ref = -INFINITY;   // exponent reference (raw score units)
+    float l_run = 0.f;         // this lane's share of the row sum (its 32 of the 64 keys per tile)
 
-    const __bf16* k_base = k + (size_t)it.row0 * row_stride + (size_t)it.head * D;
-    const __bf16* v_base = v + (size_t)it.row0 * row_stride + (size_t)it.head * D;
+    const __bf16* k_base = k + (size_t)it.row0 * row_stride + head_off;
+    const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
+    const int n_tiles = (L + C::BN - 1) / C::BN;
 
-    for (int kv0 = 0; kv0 < L; kv0 += C::BN) {
-      __syncthreads();   // the previous tile is no longer being read
+    u32x4 gk[NP], gv[NP];
+    auto fetch_tile = [&](int t) {     // global -> registers; a tile past the end reads as zeros
+      const int kv0 = t * C::BN;
+      const uint32_t bytes = (uint32_t)max(0, min(L - kv0, C::BN)) * row_bytes;
+      const auto rk = make_rsrc(k_base + (size_t)kv0 * row_stride, bytes);
+      const auto rv = make_rsrc(v_base + (size_t)kv0 * row_stride, bytes);
 #pragma unroll
-      for (int p = 0; p < C::BN / RPP; ++p) {
-        const int r = p * RPP + ld_row;
-        const bool ok = kv0 + r < L;
-        const size_t g = (size_t)(kv0 + r) * row_stride + ld_col;
-        u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (ok) {
-          kk = *reinterpret_cast<const u32x4*>(k_base + g);
-          vv = *reinterpret_cast<const u32x4*>(v_base + g);
-        }
-        *reinterpret_cast<u32x4*>(&sK[r * C::KS + ld_col]) = kk;
-        *reinterpret_cast<u32x4*>(&sV[r * C::VS + ld_col]) = vv;
+      for (int p = 0; p < NP; ++p) {
+        const uint32_t off = (uint32_t)(p * RPP + ld_row) * row_bytes + (uint32_t)ld_chunk * 16u;
+        gk[p] = buffer_load16(rk, off);
+        gv[p] = buffer_load16(rv, off);
       }
-      __syncthreads();
-
-      // S^T (64 keys x 32 queries) = K tile . Q^T
-      f32x16 s[2];
+    };
+    auto commit_tile = [&](int buf) {  // registers -> LDS
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        s[mb] = zero16();
-#pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[(32 * mb + l32) * C::KS + 16 * cc + 8 * hh]);
-          s[mb] = mfma32(a, qf[cc], s[mb]);
-        }
+      for (int p = 0; p < NP; ++p) {
+        const int o_ = TL::off(p * RPP + ld_row, ld_chunk * 8);
+        *reinterpret_cast<u32x4*>(&sK[buf][o_]) = gk[p];
+        *reinterpret_cast<u32x4*>(&sV[buf][o_]) = gv[p];
       }
-      if (kv0 + C::BN > L) {   // ragged last tile: keys past the end of the sequence
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kv = kv0 + 32 * mb + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (kv >= L) s[mb][r] = -INFINITY;
-          }
-      }
+    };
 
-      // online softmax, base 2
-      float m_loc = s[0][0];
+    // One tile: 64 keys as two halves of 32.  MASKED is the ragged last tile.
+    auto process_tile = [&](int t, auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
+      const int cur = t & 1;
+      const __bf16* tK = sK[cur];
+      const __bf16* tV = sV[cur];
+      fetch_tile(t + 1);
+
+      bf16x8 ak0[C::KC], ak1[C::KC];
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s[mb][r]);
-      m_loc = fmaxf(m_loc, xor32(m_loc));
-      const float m_new = fmaxf(m_run, m_loc);      // finite: every tile holds at least one valid key
-      const float alpha = fast_exp2((m_run - m_new) * c);
-      const float mc = m_new * c;
-      float l_loc = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int cc = 0; cc < C::KC; ++cc) ak0[cc] = tile_row_operand<D>(tK, l32, 16 * cc + 8 * hh);
+      KNAP_SCHED_FENCE();
+
+      f32x16 s0, s1;
+      if constexpr (MASKED) {   // keys past the end of the sequence start (and stay) at -inf
+        const int kv0 = t * C::BN;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = fast_exp2(__builtin_fmaf(s[mb][r], c, -mc));
-          s[mb][r] = p;
-          l_loc += p;
+          const int kv = kv0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          s0[r] = kv < L ? 0.f : -INFINITY;
+          s1[r] = kv + 32 < L ? 0.f : -INFINITY;
         }
-      l_run = l_run * alpha + l_loc;
-      m_run = m_new;
-#pragma unroll
-      for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-
-      // O^T (d x 32 queries) += V^T P^T.  Chunk cc contracts 16 keys; element e of a
-      // lane's operand is key 16 cc + 8 (e / 4) + 4 hh + e % 4 on both sides.
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const int mb = cc >> 1, r0 = 8 * (cc & 1);
-        const bf16x8 pb = pack8(s[mb][r0], s[mb][r0 + 1], s[mb][r0 + 2], s[mb][r0 + 3],
-                                s[mb][r0 + 4], s[mb][r0 + 5], s[mb][r0 + 6], s[mb][r0 + 7]);
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db) {
-          const bf16x8 a = lds_operand_tr(sV, C::VS, 16 * cc + 4 * hh, 16 * cc + 8 + 4 * hh, 32 * db, lane);
-          o[db] = mfma32(a, pb, o[db]);
-        }
+      } else {
+        s0 = zero16();
+        s1 = zero16();
       }
-    }
+      // slot 1: S^T of keys 0..31 | K fragments of keys 32..63
+#pragma unroll
+      for (int cc = 0; cc < C::KC; ++cc) s0 = mfma32(ak0[cc], qf[cc], s0);
+#pragma unroll
+      for (int cc = 0; cc < C::KC; ++cc) ak1[cc] = tile_row_operand<D>(tK, 32 + l32, 16 * cc + 8 * hh);
+#pragma unroll
+      for (int i = 0; i < C::KC; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); }
+      KNAP_SCHED_FENCE();
+
+      // slot 2: S^T of keys 32..63 | max over keys 0..31, V^T fragments of keys 0..31
+      bf16x8 vt0[2][C::DB], vt1[2][C::DB];
+#pragma unroll
+      for (int cc = 0; cc < C::KC; ++cc) s1 = mfma32(ak1[cc], qf[cc], s1);
+      float m_loc = s0[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) m_loc = fmaxf(m_loc, s0[r]);
+#pragma unroll
+      for (int ck = 0; ck < 2; ++ck)
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+          vt0[ck][db] = tile_col_operand<D>(tV, 16 * ck + 4 * hh, 16 * ck + 8 + 4 * hh, 32 * db, lane);
+#pragma unroll
+      for (int i = 0; i < C::KC; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_VALU, 2); }
+      KNAP_SCHED_FENCE();
+
+#pragma unroll
+      for (int r = 0; r < 16; ++r) m_loc = fmaxf(m_loc, s1[r]);
+      m_loc = fmaxf(m_loc, xor32(m_loc));
+      // move the reference only when the tile maximum is far above it (always on the first tile)
+      if (__builtin_amdgcn_ballot_w64((m_loc - m_ref) * c > kRescaleThreshold) != 0) {
+        const float m_new = fmaxf(m_ref, m_loc);
+        const float alpha = fast_exp2((m_ref - m_new) * c);
+        m_ref = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      }
+      const float mc = m_ref * c;
+
+      // P^T of a half, packed: element e of chunk ck is key 16 ck + 8 (e / 4) + 4 hh + e % 4
+      auto exps = [&](const f32x16& s, bf16x8 (&pb)[2]) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(__builtin_fmaf(s[r], c, -mc));
+          l_run += p[r];
+        }
+#pragma unroll
+        for (int ck = 0; ck < 2; ++ck) {
+          const int r0 = 8 * ck;
+          pb[ck] = pack8(p[r0], p[r0 + 1], p[r0 + 2], p[r0 + 3], p[r0 + 4], p[r0 + 5], p[r0 + 6], p[r0 + 7]);
+        }
+      };
+      bf16x8 pb0[2], pb1[2];
+      exps(s0, pb0);
+      KNAP_SCHED_FENCE();
+
+      // slot 3: O^T += V^T P^T over keys 0..31 | P^T of keys 32..63, V^T fragments of keys 32..63
+#pragma unroll
+      for (int ck = 0; ck < 2; ++ck)
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) o[db] = mfma32(vt0[ck][db], pb0[ck], o[db]);
+      exps(s1, pb1);
+#pragma unroll
+      for (int ck = 0; ck < 2; ++ck)
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+          vt1[ck][db] = tile_col_operand<D>(tV, 32 + 16 * ck + 4 * hh, 32 + 16 * ck + 8 + 4 * hh, 32 * db, lane);
+#pragma unroll
+      for (int i = 0; i < 2 * C::DB; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_VALU, 8); }
+      KNAP_SCHED_FENCE();
+
+      // slot 4: O^T += V^T P^T over keys 32..63 | next tile: registers -> LDS
+#pragma unroll
+      for (int ck = 0; ck < 2; ++ck)
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) o[db] = mfma32(vt1[ck][db], pb1[ck], o[db]);
+      commit_tile(cur ^ 1);
+#pragma unroll
+      for (int i = 0; i < 2 * C::DB; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_WRITE, 1); }
+      KNAP_SCHED_FENCE();
+      __syncthreads();     // next tile visible; this tile no longer read
+    };
+
+    __syncthreads();       // the previous item (or the schedule build) is done with both buffers
+    fetch_tile(0);
+    commit_tile(0);
+    __syncthreads();
+
+    const bool ragged = (L % C::BN) != 0;
+    const int n_full = ragged ? n_tiles - 1 : n_tiles;
+    for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
+    if (ragged) process_tile(n_tiles - 1, std::true_type{});
 
     // epilogue: normalise, store out (bf16) and lse (natural log)
     const float l_tot = l_run + xor32(l_run);
     const float inv = 1.0f / l_tot;
     if (q_valid) {
-      __bf16* o_ptr = out + (size_t)(it.row0 + q_row) * row_stride + (size_t)it.head * D;
+      __bf16* o_ptr = out + (size_t)(it.row0 + q_row) * row_stride + head_off;
 #pragma unroll
       for (int db = 0; db < C::DB; ++db)
 #pragma unroll
@@ -169,7 +256,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
                                   o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
           *reinterpret_cast<bf16x4*>(o_ptr + 32 * db + 8 * g + 4 * hh) = pk;
         }
-      if (hh == 0) lse[(size_t)it.head * T + it.row0 + q_row] = m_run * scale + __logf(l_tot);
+      if (hh == 0) lse[(size_t)it.head * T + it.row0 + q_row] = m_ref * scale + __logf(l_tot);
     }
   }
 }

@@ -59,6 +59,45 @@ __device__ __forceinline__ bf16x8 join(bf16x4 lo, bf16x4 hi) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// LDS tile layout for tiles of bf16 rows of D elements, addressed in 16-byte chunks.
+//  D = 128: rows are 256 B (all 64 banks), unpadded; chunk c of row r sits at position
+//           c ^ (4 (r % 4) + (r / 4) % 4).  Sixteen consecutive rows put one chunk index in
+//           sixteen different positions (128-bit row reads: no bank conflict), and four
+//           consecutive rows starting at a multiple of four put a 64-byte column strip in
+//           sixteen different positions (transposing 64-bit reads: no bank conflict).
+//  D = 64:  rows padded by 16 B (row reads conflict-free; transposing reads two-way).
+template <int D>
+struct Tile {
+  static constexpr int LD = (D == 128) ? 128 : D + 8;          // row pitch in elements
+  __device__ static __forceinline__ int chunk_pos(int row, int chunk) {
+    if constexpr (D == 128) return chunk ^ (4 * (row & 3) + ((row >> 2) & 3));
+    else return chunk;
+  }
+  // element offset of column `col` (a multiple of 4) of row `row`
+  __device__ static __forceinline__ int off(int row, int col) {
+    return row * LD + (chunk_pos(row, col >> 3) << 3) + (col & 7);
+  }
+};
+
+// 8-element MFMA operand read along a row of a Tile<D>: elements col .. col + 7 (col % 8 == 0)
+template <int D>
+__device__ __forceinline__ bf16x8 tile_row_operand(const __bf16* X, int row, int col) {
+  return *reinterpret_cast<const bf16x8*>(X + Tile<D>::off(row, col));
+}
+
+// 8-element MFMA operand whose contraction index runs down the rows of a Tile<D>: element e of
+// the lane with column n = n_base + (l % 32) is X[k_lo + e][n] for e < 4, X[k_hi + e - 4][n] else.
+// k_lo and k_hi must be multiples of 4 (they may depend on hh = lane / 32).
+template <int D>
+__device__ __forceinline__ bf16x8 tile_col_operand(const __bf16* X, int k_lo, int k_hi, int n_base, int lane) {
+  const int i = lane & 15;
+  const int n0 = n_base + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
+  const int kr = i >> 2;
+  bf16x4 lo = lds_read_tr(X + Tile<D>::off(k_lo + kr, n0));
+  bf16x4 hi = lds_read_tr(X + Tile<D>::off(k_hi + kr, n0));
+  return join(lo, hi);
+}
+
 // An 8-element MFMA operand whose contraction index runs down a row-major LDS
 // matrix X[k][n] (stride `ld` elements): element e of the lane with column
 // n = n_base + (l % 32) is X[k_lo + e][n] for e < 4 and X[k_hi + e - 4][n] else.
@@ -89,6 +128,20 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 __device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 0);
 }
+
+// Scheduling helpers.  A fence keeps the scheduler from moving anything across it; the
+// group hints inside one fenced region ask for instruction classes in the given order,
+// which is how MFMAs get interleaved with the LDS reads and arithmetic of another stage.
+#define KNAP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#if defined(KNAP_NO_SCHED_GROUPS)
+#define KNAP_SGB(mask, n) ((void)0)
+#else
+#define KNAP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#endif
+#define KNAP_SG_VALU 0x002
+#define KNAP_SG_MFMA 0x008
+#define KNAP_SG_DS_READ 0x100
+#define KNAP_SG_DS_WRITE 0x200
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
