@@ -5,8 +5,8 @@
 // One persistent workgroup (4 waves) takes work items (sequence, head, 128-row
 // query tile) from the longest-first schedule.  Wave w owns 32 query rows and
 // streams the sequence's keys and values through LDS in tiles of 64 rows; the
-// next tile travels global -> registers while the current one is used, and is
-// written to the other LDS buffer behind one barrier per tile.
+// next tile is copied global -> LDS asynchronously (no staging registers) into
+// the other buffer while the current one is used, behind one barrier per tile.
 //
 // Orientation: the scores are computed transposed, S^T = K Q^T, so that in the
 // MFMA result layout a lane holds ONE query (column l % 32) and its registers
@@ -48,12 +48,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   extern __shared__ int s_dyn[];
   int* s_order = s_dyn;
   int* s_start = s_dyn + n_seq;
-  __shared__ __attribute__((aligned(16))) __bf16 sK[2][C::TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[2][C::TILE_ELEMS];
+  // separate arrays (not one indexed array) so that reads of one buffer are known not to
+  // depend on the asynchronous copy into the other
+  __shared__ __attribute__((aligned(1024))) __bf16 sK0[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sK1[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sV0[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sV1[C::TILE_ELEMS];
   static_assert(sizeof(__bf16) * C::TILE_ELEMS >= sizeof(int) * kThreads, "scan scratch must fit in a tile");
 
   // the scan scratch of the schedule lives in the first K buffer, which is not in use yet
-  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK[0][0]));
+  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -63,13 +67,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   const float c = scale * kLog2e;
   const size_t row_stride = (size_t)H * D;
   const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
-
-  // global -> LDS tile copy geometry: 16 B per thread and pass
-  constexpr int TPR = D / 8;                 // threads (16-byte chunks) per row
-  constexpr int RPP = kThreads / TPR;        // rows per pass
-  constexpr int NP = C::BN / RPP;            // passes per tile
-  const int ld_row = tid / TPR;
-  const int ld_chunk = tid % TPR;
+  RowReader<D> k_rows;   // K tile rows -> A operands of S^T
+  ColReader<D> v_cols;   // V tile columns -> A operands of O^T += V^T P^T
+  k_rows.init(lane);
+  v_cols.init(lane);
 
   for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
@@ -99,39 +100,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
     const int n_tiles = (L + C::BN - 1) / C::BN;
 
-    u32x4 gk[NP], gv[NP];
-    auto fetch_tile = [&](int t) {     // global -> registers; a tile past the end reads as zeros
+    auto load_tile = [&](int t, __bf16* dK, __bf16* dV) {   // asynchronous; a tile past the end arrives as zeros
       const int kv0 = t * C::BN;
       const uint32_t bytes = (uint32_t)max(0, min(L - kv0, C::BN)) * row_bytes;
-      const auto rk = make_rsrc(k_base + (size_t)kv0 * row_stride, bytes);
-      const auto rv = make_rsrc(v_base + (size_t)kv0 * row_stride, bytes);
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const uint32_t off = (uint32_t)(p * RPP + ld_row) * row_bytes + (uint32_t)ld_chunk * 16u;
-        gk[p] = buffer_load16(rk, off);
-        gv[p] = buffer_load16(rv, off);
-      }
-    };
-    auto commit_tile = [&](int buf) {  // registers -> LDS
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const int o_ = TL::off(p * RPP + ld_row, ld_chunk * 8);
-        *reinterpret_cast<u32x4*>(&sK[buf][o_]) = gk[p];
-        *reinterpret_cast<u32x4*>(&sV[buf][o_]) = gv[p];
-      }
+      tile_load_async<D>(dK, make_rsrc(k_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
+      tile_load_async<D>(dV, make_rsrc(v_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
     };
 
     // One tile: 64 keys as two halves of 32.  MASKED is the ragged last tile.
-    auto process_tile = [&](int t, auto masked_tag) {
+    auto process_tile = [&](int t, auto masked_tag, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
       constexpr bool MASKED = decltype(masked_tag)::value;
-      const int cur = t & 1;
-      const __bf16* tK = sK[cur];
-      const __bf16* tV = sV[cur];
-      fetch_tile(t + 1);
+      load_tile(t + 1, nK, nV);
 
       bf16x8 ak0[C::KC], ak1[C::KC];
 #pragma unroll
-      for (int cc = 0; cc < C::KC; ++cc) ak0[cc] = tile_row_operand<D>(tK, l32, 16 * cc + 8 * hh);
+      for (int cc = 0; cc < C::KC; ++cc) ak0[cc] = k_rows.get(tK, 0, cc);
       KNAP_SCHED_FENCE();
 
       f32x16 s0, s1;
@@ -151,7 +134,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
 #pragma unroll
       for (int cc = 0; cc < C::KC; ++cc) s0 = mfma32(ak0[cc], qf[cc], s0);
 #pragma unroll
-      for (int cc = 0; cc < C::KC; ++cc) ak1[cc] = tile_row_operand<D>(tK, 32 + l32, 16 * cc + 8 * hh);
+      for (int cc = 0; cc < C::KC; ++cc) ak1[cc] = k_rows.get(tK, 32, cc);
 #pragma unroll
       for (int i = 0; i < C::KC; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); }
       KNAP_SCHED_FENCE();
@@ -164,12 +147,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
 #pragma unroll
       for (int r = 1; r < 16; ++r) m_loc = fmaxf(m_loc, s0[r]);
 #pragma unroll
-      for (int ck = 0; ck < 2; ++ck)
-#pragma unroll
         for (int db = 0; db < C::DB; ++db)
-          vt0[ck][db] = tile_col_operand<D>(tV, 16 * ck + 4 * hh, 16 * ck + 8 + 4 * hh, 32 * db, lane);
+          vt0[0][db] = v_cols.get(tV, 0, db);
 #pragma unroll
-      for (int i = 0; i < C::KC; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_VALU, 2); }
+      for (int i = 0; i < C::KC; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); KNAP_SGB(KNAP_SG_VALU, 2); }
       KNAP_SCHED_FENCE();
 
 #pragma unroll
@@ -203,45 +184,53 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
         }
       };
       bf16x8 pb0[2], pb1[2];
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+          vt0[1][db] = v_cols.get(tV, 16, db);
       exps(s0, pb0);
       KNAP_SCHED_FENCE();
 
-      // slot 3: O^T += V^T P^T over keys 0..31 | P^T of keys 32..63, V^T fragments of keys 32..63
+      // slot 3: O^T += V^T P^T over keys 0..31 | P^T of keys 32..63, V^T fragments of keys 32..47
 #pragma unroll
       for (int ck = 0; ck < 2; ++ck)
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) o[db] = mfma32(vt0[ck][db], pb0[ck], o[db]);
       exps(s1, pb1);
 #pragma unroll
-      for (int ck = 0; ck < 2; ++ck)
+      for (int db = 0; db < C::DB; ++db) vt1[0][db] = v_cols.get(tV, 32, db);
 #pragma unroll
-        for (int db = 0; db < C::DB; ++db)
-          vt1[ck][db] = tile_col_operand<D>(tV, 32 + 16 * ck + 4 * hh, 32 + 16 * ck + 8 + 4 * hh, 32 * db, lane);
-#pragma unroll
-      for (int i = 0; i < 2 * C::DB; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_VALU, 8); }
+      for (int i = 0; i < 2 * C::DB; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); KNAP_SGB(KNAP_SG_VALU, 8); }
       KNAP_SCHED_FENCE();
 
-      // slot 4: O^T += V^T P^T over keys 32..63 | next tile: registers -> LDS
+      // slot 4: O^T += V^T P^T over keys 32..63 | V^T fragments of keys 48..63
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) vt1[1][db] = v_cols.get(tV, 48, db);
 #pragma unroll
       for (int ck = 0; ck < 2; ++ck)
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) o[db] = mfma32(vt1[ck][db], pb1[ck], o[db]);
-      commit_tile(cur ^ 1);
 #pragma unroll
-      for (int i = 0; i < 2 * C::DB; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_WRITE, 1); }
+      for (int i = 0; i < C::DB; ++i) { KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_MFMA, 1); }
       KNAP_SCHED_FENCE();
+      wait_async_loads();
       __syncthreads();     // next tile visible; this tile no longer read
     };
 
     __syncthreads();       // the previous item (or the schedule build) is done with both buffers
-    fetch_tile(0);
-    commit_tile(0);
+    load_tile(0, sK0, sV0);
+    wait_async_loads();
     __syncthreads();
 
     const bool ragged = (L % C::BN) != 0;
     const int n_full = ragged ? n_tiles - 1 : n_tiles;
-    for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
-    if (ragged) process_tile(n_tiles - 1, std::true_type{});
+    for (int t = 0; t < n_full; t += 2) {
+      process_tile(t, std::false_type{}, sK0, sV0, sK1, sV1);
+      if (t + 1 < n_full) process_tile(t + 1, std::false_type{}, sK1, sV1, sK0, sV0);
+    }
+    if (ragged) {
+      if ((n_tiles - 1) & 1) process_tile(n_tiles - 1, std::true_type{}, sK1, sV1, sK0, sV0);
+      else process_tile(n_tiles - 1, std::true_type{}, sK0, sV0, sK1, sV1);
+    }
 
     // epilogue: normalise, store out (bf16) and lse (natural log)
     const float l_tot = l_run + xor32(l_run);

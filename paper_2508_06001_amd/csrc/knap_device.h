@@ -65,13 +65,15 @@ __device__ __forceinline__ bf16x8 join(bf16x4 lo, bf16x4 hi) {
 //           sixteen different positions (128-bit row reads: no bank conflict), and four
 //           consecutive rows starting at a multiple of four put a 64-byte column strip in
 //           sixteen different positions (transposing 64-bit reads: no bank conflict).
-//  D = 64:  rows padded by 16 B (row reads conflict-free; transposing reads two-way).
+//  D = 64:  rows are 128 B; chunk c of row r sits at position c ^ ((r / 2) % 8) (row reads
+//           conflict-free, transposing reads partly two-way).
 template <int D>
 struct Tile {
-  static constexpr int LD = (D == 128) ? 128 : D + 8;          // row pitch in elements
+  static constexpr int LD = D;                                  // row pitch in elements (no padding)
+  static constexpr int CPR = D / 8;                             // 16-byte chunks per row
   __device__ static __forceinline__ int chunk_pos(int row, int chunk) {
     if constexpr (D == 128) return chunk ^ (4 * (row & 3) + ((row >> 2) & 3));
-    else return chunk;
+    else return chunk ^ ((row >> 1) & 7);                       // D = 64: two rows per 256 B of banks
   }
   // element offset of column `col` (a multiple of 4) of row `row`
   __device__ static __forceinline__ int off(int row, int col) {
@@ -79,24 +81,73 @@ struct Tile {
   }
 };
 
-// 8-element MFMA operand read along a row of a Tile<D>: elements col .. col + 7 (col % 8 == 0)
+// Asynchronous global -> LDS copy of `rows` x D bf16 rows into a Tile<D> (rows a multiple of
+// 4 waves x 1 KB), straight into the swizzled layout: a wave instruction fills 1 KB of LDS,
+// lane l supplying the 16 bytes that belong at offset 16 l, whatever global chunk that is.
+// `r` covers the valid bytes of the source rows (pitch row_bytes); rows past it arrive as
+// zeros.  Completion: s_waitcnt vmcnt(0) by every wave, then a workgroup barrier.
 template <int D>
-__device__ __forceinline__ bf16x8 tile_row_operand(const __bf16* X, int row, int col) {
-  return *reinterpret_cast<const bf16x8*>(X + Tile<D>::off(row, col));
+__device__ __forceinline__ void tile_load_async(__bf16* tile, __amdgpu_buffer_rsrc_t r, uint32_t row_bytes,
+                                                int rows, int wave, int lane) {
+  constexpr int CPR = Tile<D>::CPR;
+  constexpr int ROWS_PER_INSTR = 64 / CPR;                       // 4 (D = 128) or 8 (D = 64)
+  const int n_instr = rows / (4 * ROWS_PER_INSTR);               // per wave
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (i < n_instr) {
+      const int row_base = (wave * n_instr + i) * ROWS_PER_INSTR;
+      const int row = row_base + lane / CPR;
+      const int chunk = Tile<D>::chunk_pos(row, lane % CPR);     // the swizzle is its own inverse
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          r, (__attribute__((address_space(3))) void*)(tile + row_base * Tile<D>::LD), 16,
+          (int)((uint32_t)row * row_bytes + (uint32_t)chunk * 16u), 0, 0, 0);
+    }
+  }
 }
 
-// 8-element MFMA operand whose contraction index runs down the rows of a Tile<D>: element e of
-// the lane with column n = n_base + (l % 32) is X[k_lo + e][n] for e < 4, X[k_hi + e - 4][n] else.
-// k_lo and k_hi must be multiples of 4 (they may depend on hh = lane / 32).
+__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// The swizzle only looks at the low four bits of the row, so a read at (row_base + r, col)
+// with row_base a multiple of 16 is the read at (r, col) moved by row_base whole rows.  The
+// two readers below keep the few lane-dependent offsets of a wave's access patterns in
+// registers once and for all; everything else becomes an immediate offset of the LDS read.
+
+// 128-bit row reads: the lane with l32 = lane % 32 reads elements 16 cc + 8 hh .. + 7 of row
+// row_base + l32 (row_base a multiple of 32): an MFMA A or B operand whose contraction index
+// runs along the row.
 template <int D>
-__device__ __forceinline__ bf16x8 tile_col_operand(const __bf16* X, int k_lo, int k_hi, int n_base, int lane) {
-  const int i = lane & 15;
-  const int n0 = n_base + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
-  const int kr = i >> 2;
-  bf16x4 lo = lds_read_tr(X + Tile<D>::off(k_lo + kr, n0));
-  bf16x4 hi = lds_read_tr(X + Tile<D>::off(k_hi + kr, n0));
-  return join(lo, hi);
-}
+struct RowReader {
+  int off[D / 16];
+  __device__ __forceinline__ void init(int lane) {
+    const int l32 = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int cc = 0; cc < D / 16; ++cc) off[cc] = Tile<D>::off(l32, 16 * cc + 8 * hh);
+  }
+  __device__ __forceinline__ bf16x8 get(const __bf16* tile, int row_base, int cc) const {
+    return *reinterpret_cast<const bf16x8*>(tile + row_base * Tile<D>::LD + off[cc]);
+  }
+};
+
+// Transposing reads: an MFMA operand whose contraction index runs down the rows.  Element e
+// of the lane with column 32 db + lane % 32 is X[k_base + 8 (e / 4) + 4 hh + e % 4][column]
+// (k_base a multiple of 16): the index permutation under which an MFMA result in registers
+// is, unchanged, the other operand.
+template <int D>
+struct ColReader {
+  int off[D / 32][2];
+  __device__ __forceinline__ void init(int lane) {
+    const int i = lane & 15, kr = i >> 2, hh = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int hi = 0; hi < 2; ++hi)
+        off[db][hi] = Tile<D>::off(4 * hh + kr + 8 * hi, 32 * db + ((lane >> 4) & 1) * 16 + 4 * (i & 3));
+  }
+  __device__ __forceinline__ bf16x8 get(const __bf16* tile, int k_base, int db) const {
+    const __bf16* p = tile + k_base * Tile<D>::LD;
+    return join(lds_read_tr(p + off[db][0]), lds_read_tr(p + off[db][1]));
+  }
+};
 
 // An 8-element MFMA operand whose contraction index runs down a row-major LDS
 // matrix X[k][n] (stride `ld` elements): element e of the lane with column
