@@ -302,10 +302,9 @@ template <int D>
 struct DqCfg {
   static constexpr int BM = 128;         // query rows per work item
   static constexpr int BN = 64;          // key/value rows per LDS tile
-  static constexpr int KS = D + 40;      // K tile row stride: read row-wise (S^T) and transposed (dQ^T)
-  static constexpr int VS = D + 8;       // V tile row stride: row-wise 128-bit reads only
   static constexpr int KC = D / 16;
   static constexpr int DB = D / 32;
+  static constexpr int TILE_ELEMS = BN * Tile<D>::LD;
 };
 
 template <int D>
@@ -318,11 +317,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   extern __shared__ int s_dyn[];
   int* s_order = s_dyn;
   int* s_start = s_dyn + n_seq;
-  __shared__ int s_part[kThreads];
-  __shared__ __attribute__((aligned(16))) __bf16 sK[C::BN * C::KS];
-  __shared__ __attribute__((aligned(16))) __bf16 sV[C::BN * C::VS];
+  // K is read row-wise (S^T) and transposed (dQ^T), V row-wise (dP^T); two buffers each, as
+  // separate arrays so that reads of one are known not to depend on the copy into the other
+  __shared__ __attribute__((aligned(1024))) __bf16 sK0[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sK1[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sV0[C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 sV1[C::TILE_ELEMS];
+  static_assert(sizeof(__bf16) * C::TILE_ELEMS >= sizeof(int) * kThreads, "scan scratch must fit in a tile");
 
-  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, s_part);
+  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -331,90 +334,105 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
   const size_t row_stride = (size_t)H * D;
-
-  constexpr int TPR = D / 8;
-  constexpr int RPP = kThreads / TPR;
-  const int ld_row = tid / TPR;
-  const int ld_col = (tid % TPR) * 8;
+  const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
+  RowReader<D> rows;     // K and V tile rows -> A operands of S^T and dP^T
+  ColReader<D> cols;     // K tile columns -> A operands of dQ^T += K^T dS^T
+  rows.init(lane);
+  cols.init(lane);
 
   for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
-    const int q_row = it.tile * C::BM + wave * 32 + l32;
+    const int q0 = it.tile * C::BM;
+    const int q_row = q0 + wave * 32 + l32;
     const bool q_valid = q_row < L;
-    const size_t q_off = (size_t)(it.row0 + q_row) * row_stride + (size_t)it.head * D;
+    const size_t head_off = (size_t)it.head * D;
 
+    // this lane's q and dO rows as B operands (rows past the end read as zero)
     bf16x8 qf[C::KC], dof[C::KC];
+    {
+      const uint32_t bytes = (uint32_t)min(L - q0, C::BM) * row_bytes;
+      const auto rq = make_rsrc(q + (size_t)(it.row0 + q0) * row_stride + head_off, bytes);
+      const auto rd = make_rsrc(dout + (size_t)(it.row0 + q0) * row_stride + head_off, bytes);
+      const uint32_t off = (uint32_t)(wave * 32 + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
 #pragma unroll
-    for (int cc = 0; cc < C::KC; ++cc) {
-      qf[cc] = q_valid ? *reinterpret_cast<const bf16x8*>(q + q_off + 16 * cc + 8 * hh) : zero_bf16x8();
-      dof[cc] = q_valid ? *reinterpret_cast<const bf16x8*>(dout + q_off + 16 * cc + 8 * hh) : zero_bf16x8();
+      for (int cc = 0; cc < C::KC; ++cc) {
+        qf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rq, off + 32u * cc));
+        dof[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rd, off + 32u * cc));
+      }
     }
     // per-lane scalars of this lane's query; +inf LSE turns rows past the end into P = 0
-    const float lse2 = q_valid ? lse[(size_t)it.head * T + it.row0 + q_row] * kLog2e : INFINITY;
-    const float dl = q_valid ? delta[(size_t)it.head * T + it.row0 + q_row] : 0.f;
+    const int q_idx = q_valid ? q_row : 0;
+    const float lse_raw = lse[(size_t)it.head * T + it.row0 + q_idx];
+    const float dl_raw = delta[(size_t)it.head * T + it.row0 + q_idx];
+    const float lse2 = q_valid ? lse_raw * kLog2e : INFINITY;
+    const float dl = q_valid ? dl_raw : 0.f;
 
     f32x16 acc[C::DB];
 #pragma unroll
     for (int db = 0; db < C::DB; ++db) acc[db] = zero16();
 
-    const __bf16* k_base = k + (size_t)it.row0 * row_stride + (size_t)it.head * D;
-    const __bf16* v_base = v + (size_t)it.row0 * row_stride + (size_t)it.head * D;
+    const __bf16* k_base = k + (size_t)it.row0 * row_stride + head_off;
+    const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
+    const int n_tiles = (L + C::BN - 1) / C::BN;
 
-    for (int kv0 = 0; kv0 < L; kv0 += C::BN) {
-      __syncthreads();
-#pragma unroll
-      for (int p = 0; p < C::BN / RPP; ++p) {
-        const int r = p * RPP + ld_row;
-        const size_t g = (size_t)(kv0 + r) * row_stride + ld_col;
-        u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (kv0 + r < L) {   // rows past the end stay zero: they then add nothing to dQ
-          kk = *reinterpret_cast<const u32x4*>(k_base + g);
-          vv = *reinterpret_cast<const u32x4*>(v_base + g);
-        }
-        *reinterpret_cast<u32x4*>(&sK[r * C::KS + ld_col]) = kk;
-        *reinterpret_cast<u32x4*>(&sV[r * C::VS + ld_col]) = vv;
-      }
-      __syncthreads();
+    // asynchronous; rows past the end arrive as zeros and add nothing to dQ
+    auto load_tile = [&](int t, __bf16* dK, __bf16* dV) {
+      const int kv0 = t * C::BN;
+      const uint32_t bytes = (uint32_t)max(0, min(L - kv0, C::BN)) * row_bytes;
+      tile_load_async<D>(dK, make_rsrc(k_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
+      tile_load_async<D>(dV, make_rsrc(v_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
+    };
 
-      // S^T = K Q^T and dP^T = V dO^T: (64 keys) x (32 queries)
-      f32x16 s[2], dp[2];
+    // One tile: 64 keys as two halves of 32, one after the other (the register file is full with
+    // the q and dO fragments and the dQ accumulator; the second wave of the SIMD fills the gaps).
+    // Within a half the LDS reads are streamed a few MFMAs ahead of their use.
+    auto process_tile = [&](int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
+      load_tile(t + 1, nK, nV);
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        s[mb] = zero16();
-        dp[mb] = zero16();
+      for (int half = 0; half < 2; ++half) {
+        f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int cc = 0; cc < C::KC; ++cc) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&sK[(32 * mb + l32) * C::KS + 16 * cc + 8 * hh]);
-          const bf16x8 av = *reinterpret_cast<const bf16x8*>(&sV[(32 * mb + l32) * C::VS + 16 * cc + 8 * hh]);
-          s[mb] = mfma32(ak, qf[cc], s[mb]);
-          dp[mb] = mfma32(av, dof[cc], dp[mb]);
+          s = mfma32(rows.get(tK, 32 * half, cc), qf[cc], s);
+          dp = mfma32(rows.get(tV, 32 * half, cc), dof[cc], dp);
         }
+        // K^T fragments of the first 16 keys are requested before the arithmetic
+        bf16x8 kt0[C::DB];
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) kt0[db] = cols.get(tK, 32 * half, db);
+#pragma unroll
+        for (int i = 0; i < 2 * C::KC; ++i) { KNAP_SGB(KNAP_SG_DS_READ, 1); KNAP_SGB(KNAP_SG_MFMA, 1); }
+        KNAP_SCHED_FENCE();
+        // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2); element e of chunk ck is key
+        // 32 half + 16 ck + 8 (e / 4) + 4 hh + e % 4
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse2)) * (dp[r] - dl);
+        const bf16x8 d0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+        const bf16x8 d1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        KNAP_SCHED_FENCE();
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) acc[db] = mfma32(kt0[db], d0, acc[db]);
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) acc[db] = mfma32(cols.get(tK, 32 * half + 16, db), d1, acc[db]);
+        KNAP_SCHED_FENCE();
       }
-      // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2)
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = fast_exp2(__builtin_fmaf(s[mb][r], c, -lse2));
-          s[mb][r] = p * (dp[mb][r] - dl);
-        }
-      // dQ^T (d x 32 queries) += K^T dS^T; element e of chunk cc is key 16 cc + 8 (e / 4) + 4 hh + e % 4
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const int mb = cc >> 1, r0 = 8 * (cc & 1);
-        const bf16x8 db_ = pack8(s[mb][r0], s[mb][r0 + 1], s[mb][r0 + 2], s[mb][r0 + 3],
-                                 s[mb][r0 + 4], s[mb][r0 + 5], s[mb][r0 + 6], s[mb][r0 + 7]);
-#pragma unroll
-        for (int db = 0; db < C::DB; ++db) {
-          const bf16x8 a = lds_operand_tr(sK, C::KS, 16 * cc + 4 * hh, 16 * cc + 8 + 4 * hh, 32 * db, lane);
-          acc[db] = mfma32(a, db_, acc[db]);
-        }
-      }
+      wait_async_loads();
+      __syncthreads();     // next tile visible; this tile no longer read
+    };
+
+    __syncthreads();       // the previous item (or the schedule build) is done with both buffers
+    load_tile(0, sK0, sV0);
+    wait_async_loads();
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t += 2) {
+      process_tile(t, sK0, sV0, sK1, sV1);
+      if (t + 1 < n_tiles) process_tile(t + 1, sK1, sV1, sK0, sV0);
     }
 
     if (q_valid) {
-      __bf16* o_ptr = dq + q_off;
+      __bf16* o_ptr = dq + (size_t)(it.row0 + q_row) * row_stride + head_off;
 #pragma unroll
       for (int db = 0; db < C::DB; ++db)
 #pragma unroll
