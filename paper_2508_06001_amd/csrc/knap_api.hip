@@ -45,8 +45,10 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int check_common(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d) {
+int check_common(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
+                 float scale) {
   if (n_seq < 0 || H <= 0 || (d != 64 && d != 128)) return KNAP_ERR_INVALID_ARG;
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) return KNAP_ERR_INVALID_ARG;   // positive and finite
   if (n_seq > KNAP_MAX_SEQS) return KNAP_ERR_TOO_MANY_SEQS;
   if (n_seq == 0) return KNAP_OK;
   if (!q || !k || !v || !cu) return KNAP_ERR_INVALID_ARG;
@@ -62,7 +64,7 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
                          const int32_t* cu_seqlens, int n_seq,
                          int H, int d, float scale,
                          void* out, float* lse, void* stream) {
-  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d);
+  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d, scale);
   if (rc != KNAP_OK) return rc;
   if (n_seq == 0) return KNAP_OK;
   if (!out || !lse || !aligned(out, 16) || !aligned(lse, 4)) return KNAP_ERR_INVALID_ARG;
@@ -89,7 +91,7 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          void* dq, void* dk, void* dv,
                          int64_t total_tokens,
                          void* workspace, size_t workspace_bytes, void* stream) {
-  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d);
+  const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d, scale);
   if (rc != KNAP_OK) return rc;
   if (total_tokens < 0 || total_tokens > INT32_MAX) return KNAP_ERR_INVALID_ARG;
   if (n_seq == 0 || total_tokens == 0) return KNAP_OK;

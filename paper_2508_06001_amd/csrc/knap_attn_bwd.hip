@@ -39,7 +39,7 @@ struct BwdCfg {
   static constexpr int MB = BM / 32;
   static constexpr int NB = D / 32;
   static constexpr int KC = D / 16;
-  static constexpr int QS = D + 40;        // Q / dO tile row stride (elements); read both row-wise and transposed
+  static constexpr int TILE_ELEMS = BM * Tile<D>::LD;   // Q / dO tiles: read both row-wise and transposed
 };
 
 // delta[h][t] = sum_c dout[t][h][c] * out[t][h][c]
@@ -80,8 +80,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
   int* s_start = s_dyn + n_seq;
   __shared__ int s_part[kThreads];
   // two copies of the query-side tiles: the next step's tile lands while this one is used
-  __shared__ __attribute__((aligned(16))) __bf16 sQ[2][C::BM * C::QS];
-  __shared__ __attribute__((aligned(16))) __bf16 sdO[2][C::BM * C::QS];
+  __shared__ __attribute__((aligned(16))) __bf16 sQ[2][C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 sdO[2][C::TILE_ELEMS];
   __shared__ __attribute__((aligned(16))) float sLse[2][C::BM];     // LSE in base 2; +inf for rows past the end
   __shared__ __attribute__((aligned(16))) float sDelta[2][C::BM];
 
@@ -101,6 +101,10 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
   constexpr int NP = C::BM / RPP;            // 16-byte loads per thread and tensor per tile
   const int ld_row = tid / TPR;
   const int ld_col = (tid % TPR) * 8;
+  RowReader<D> rows;     // Q and dO tile rows -> A operands of S and dP
+  ColReader<D> cols;     // dO and Q tile columns -> B operands of dV += P^T dO and dK += dS^T Q
+  rows.init(lane);
+  cols.init(lane);
 
   for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
     const WorkItem it = decode_item<C::BN>(w, cu, n_seq, s_order, s_start);
@@ -156,9 +160,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
     auto commit_tile = [&](int buf) {           // registers -> LDS
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
-        const int r = p * RPP + ld_row;
-        *reinterpret_cast<u32x4*>(&sQ[buf][r * C::QS + ld_col]) = gq[p];
-        *reinterpret_cast<u32x4*>(&sdO[buf][r * C::QS + ld_col]) = gd[p];
+        const int o_ = Tile<D>::off(p * RPP + ld_row, ld_col);
+        *reinterpret_cast<u32x4*>(&sQ[buf][o_]) = gq[p];
+        *reinterpret_cast<u32x4*>(&sdO[buf][o_]) = gd[p];
       }
       sLse[buf][tid & (C::BM - 1)] = g_lse;
       sDelta[buf][tid & (C::BM - 1)] = g_delta;
@@ -188,9 +192,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
       auto read_rows = [&](int mb, bf16x8 (&aq)[C::KC], bf16x8 (&ad)[C::KC]) {
 #pragma unroll
         for (int cc = 0; cc < C::KC; ++cc) {
-          const int off = (32 * mb + l32) * C::QS + 16 * cc + 8 * hh;
-          aq[cc] = *reinterpret_cast<const bf16x8*>(&tQ[off]);
-          ad[cc] = *reinterpret_cast<const bf16x8*>(&tdO[off]);
+          aq[cc] = rows.get(tQ, 32 * mb, cc);
+          ad[cc] = rows.get(tdO, 32 * mb, cc);
         }
       };
       auto read_transposed = [&](int mb, bf16x8 (&bo)[2][C::NB], bf16x8 (&bq)[2][C::NB]) {
@@ -198,9 +201,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
         for (int cq = 0; cq < 2; ++cq)
 #pragma unroll
           for (int nb = 0; nb < C::NB; ++nb) {
-            const int k_lo = 32 * mb + 16 * cq + 4 * hh;
-            bo[cq][nb] = lds_operand_tr(tdO, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
-            bq[cq][nb] = lds_operand_tr(tQ, C::QS, k_lo, k_lo + 8, 32 * nb, lane);
+            bo[cq][nb] = cols.get(tdO, 32 * mb + 16 * cq, nb);
+            bq[cq][nb] = cols.get(tQ, 32 * mb + 16 * cq, nb);
           }
       };
       auto scores = [&](const bf16x8 (&aq)[C::KC], const bf16x8 (&ad)[C::KC], f32x16& s, f32x16& dp) {

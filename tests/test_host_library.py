@@ -34,6 +34,8 @@ def test_attention_entry_points_reject_bad_arguments_without_touching_a_gpu():
     assert f(16, 16, 16, 16, 1, 0, 64, 0.125, 16, 16, 0) == K.KNAP_ERR_INVALID_ARG
     assert f(8, 16, 16, 16, 1, 2, 64, 0.125, 16, 16, 0) == K.KNAP_ERR_INVALID_ARG    # misaligned q
     assert f(16, 16, 16, 16, K.KNAP_MAX_SEQS + 1, 2, 64, 0.125, 16, 16, 0) == K.KNAP_ERR_TOO_MANY_SEQS
+    for bad_scale in (0.0, -0.125, float("inf"), float("nan")):
+        assert f(16, 16, 16, 16, 1, 2, 64, bad_scale, 16, 16, 0) == K.KNAP_ERR_INVALID_ARG
     g = K.lib.knap_varlen_attn_bwd
     assert g(0, 0, 0, 0, 0, 2, 64, 0.125, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == K.KNAP_OK
     assert g(256, 512, 768, 1024, 1, 2, 64, 0.125, 1280, 1536, 1792, 2048, 2304, 2560, 100, 0, 0, 0) \
