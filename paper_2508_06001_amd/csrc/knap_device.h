@@ -209,6 +209,33 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
   return r;
 }
 
+// Packs eight fp32 values into an MFMA operand and adds the eight ROUNDED values to `acc`
+// (v_dot2c_f32_bf16 against ones).  Taking the row sum over the rounded probabilities, the
+// ones the MFMA multiplies, makes the effective attention weights of a row sum to one exactly.
+// The dot products are fed from the individually packed pairs: extracting dwords from the
+// assembled 128-bit operand is miscompiled by this compiler (every extract reads dword 0).
+__device__ __forceinline__ bf16x8 pack8_sum(float a0, float a1, float a2, float a3,
+                                            float a4, float a5, float a6, float a7, float& acc) {
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
+  bf16x2 p0, p1, p2, p3;
+  p0[0] = (__bf16)a0; p0[1] = (__bf16)a1;
+  p1[0] = (__bf16)a2; p1[1] = (__bf16)a3;
+  p2[0] = (__bf16)a4; p2[1] = (__bf16)a5;
+  p3[0] = (__bf16)a6; p3[1] = (__bf16)a7;
+  acc = __builtin_amdgcn_fdot2_f32_bf16(p0, ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(p1, ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(p3, ones, acc, false);
+  u32x4 w;
+  w[0] = __builtin_bit_cast(uint32_t, p0);
+  w[1] = __builtin_bit_cast(uint32_t, p1);
+  w[2] = __builtin_bit_cast(uint32_t, p2);
+  w[3] = __builtin_bit_cast(uint32_t, p3);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
 __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
   bf16x4 r;
   r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
