@@ -200,6 +200,17 @@ def cpu_baseline(bag, bits, budget_s: float = 20.0):
     }
 
 
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if not measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[workload][kernel]["bytes_per_launch"]
+    except Exception:
+        return None
+
+
 def run_default(args):
     import torch
     import paper_2508_06001_amd as K
@@ -212,6 +223,12 @@ def run_default(args):
         bits, dev = device_inputs(bag)
     else:
         bits, dev = None, device_inputs_fast(bag)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ev = HipEvents()
     r = time_bag(bag, dev, args.steps, args.warmup, ev)
     ms = r["gpu_ms_per_step"]
@@ -238,7 +255,8 @@ def run_default(args):
         "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel", "achieved": round(bwd_main_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_main_tflops / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_ms": round(r["bwd_main_ms"], 4),
-                     "flops_per_launch": flops_dkdv_kernel(bag), "traffic": None},
+                     "flops_per_launch": flops_dkdv_kernel(bag),
+                     "traffic": measured_traffic(f"configs[{args.config}]", "attn_bwd_dkdv_kernel")},
     }
     if not args.no_cpu_baseline:
         if bits is None:
@@ -251,47 +269,80 @@ def run_default(args):
 
 
 def run_fit(args):
-    """Cost-model experiment (Sec. 3.1 / Fig. 2 analogue): fit a, b of t = a sumL2 + b sumL on
-    single-sequence bags, then report the relative residual on the benchmark bags and random bags."""
+    """Cost-model experiment (Sec. 3.1 / Fig. 2 analogue): fit a, b of t = a sum(L^2) + b sum(L) by
+    relative least squares (the library's knap_fit_cost_model), then report the relative residual of
+    the model on the benchmark bags and on further random draws of them.
+
+    Calibration bags hold n equal sequences with n L close to the token count of the bag family
+    (65536 tokens for H = 24, 196608 for H = 3): the model prices a sequence inside a full bag, so the
+    calibration has to fill the GPU too (a single short sequence measures launch latency instead)."""
     import torch
     import paper_2508_06001_amd as K
     from knap_inputs import BagSpec, config_bag
 
     ev = HipEvents()
     report = {"families": {}}
-    for fam, (H, d) in {"H24_d128": (24, 128), "H3_d128": (3, 128)}.items():
+    for fam, (H, d, tokens) in {"H24_d128": (24, 128, 65536), "H3_d128": (3, 128, 196608)}.items():
         cal_L = [256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536] + ([131072] if H == 3 else [])
         rows = []
         for L in cal_L:
-            bag = BagSpec(f"cal{L}", [L], H=H, d=d, seed=1234 + L)
+            n = max(1, tokens // L)
+            bag = BagSpec(f"cal{L}x{n}", [L] * n, H=H, d=d, seed=1234 + L)
             dev = device_inputs_fast(bag)
             r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
-            rows.append({"L": L, "ms": r["gpu_ms_per_step"],
-                         "tflops": 14.0 * H * d * L * L / (r["gpu_ms_per_step"] * 1e-3) / 1e12})
-            log(f"[fit] {fam} L={L}: {rows[-1]['ms']:.3f} ms, {rows[-1]['tflops']:.1f} TF/s")
+            rows.append({"L": L, "n": n, "ms": r["gpu_ms_per_step"],
+                         "tflops": 14.0 * H * d * bag.sum_l2 / (r["gpu_ms_per_step"] * 1e-3) / 1e12})
+            log(f"[fit] {fam} {n} x L={L}: {rows[-1]['ms']:.3f} ms, {rows[-1]['tflops']:.1f} TF/s")
             del dev, r
             torch.cuda.empty_cache()
-        s2 = [float(r["L"]) ** 2 for r in rows]
-        s1 = [float(r["L"]) for r in rows]
+        s2 = [float(r["n"]) * float(r["L"]) ** 2 for r in rows]
+        s1 = [float(r["n"]) * float(r["L"]) for r in rows]
         t = [r["ms"] for r in rows]
         a, b, resid = K.knap_fit_cost_model(s2, s1, t)
+        log(f"[fit] {fam}: a = {a:.4e} ms/token^2, b = {b:.4e} ms/token, calibration max residual {resid * 100:.1f}%")
         evals = []
         cfgs = [1, 2, 3] if H == 24 else [4]
         for ci in cfgs:
-            for so in range(3 if ci != 4 else 1):
+            for so in range(4 if ci != 4 else 1):
                 bag = config_bag(ci, seed_offset=so)
                 dev = device_inputs_fast(bag)
                 r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
                 pred = a * bag.sum_l2 + b * bag.total_tokens
-                evals.append({"config": ci, "seed_offset": so, "T": bag.total_tokens, "sum_l2": bag.sum_l2,
-                              "ms": r["gpu_ms_per_step"], "pred_ms": pred,
+                evals.append({"config": ci, "seed_offset": so, "n_seq": len(bag.seq_lens), "T": bag.total_tokens,
+                              "sum_l2": bag.sum_l2, "ms": r["gpu_ms_per_step"], "pred_ms": pred,
                               "rel_resid": abs(r["gpu_ms_per_step"] - pred) / r["gpu_ms_per_step"]})
                 log(f"[fit] {fam} cfg{ci}/{so}: measured {r['gpu_ms_per_step']:.3f} ms, model {pred:.3f} ms, "
                     f"resid {evals[-1]['rel_resid'] * 100:.1f}%")
                 del dev, r
                 torch.cuda.empty_cache()
-        report["families"][fam] = {"a_ms_per_tok2": a, "b_ms_per_tok": b, "calibration_max_rel_resid": resid,
+        report["families"][fam] = {"a_ms_per_token2": a, "b_ms_per_token": b, "calibration_max_rel_resid": resid,
                                    "calibration": rows, "evaluation": evals}
+    # greedy demo (Sec. 3.3): a pool of sequences split into 8 one-GPU bags by the C balancer; every bag is
+    # timed on this GPU; modelled vs measured imbalance
+    fam = report["families"]["H24_d128"]
+    a, b = fam["a_ms_per_token2"], fam["b_ms_per_token"]
+    pool = []
+    for so in range(10, 16):
+        pool += config_bag(2, seed_offset=so).seq_lens
+    bag_of, load = K.knap_greedy_assign(pool, [1] * 8, a, b)
+    measured = []
+    for j in range(8):
+        lens, _ = K.knap_bag_cu_seqlens(pool, bag_of, j)
+        bag = BagSpec(f"greedy{j}", lens, H=24, d=128, seed=4000 + j)
+        dev = device_inputs_fast(bag)
+        r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+        measured.append(r["gpu_ms_per_step"])
+        log(f"[fit] greedy bag {j}: {len(lens)} seqs, {sum(lens)} tokens, model {load[j]:.3f} ms, measured {measured[-1]:.3f} ms")
+        del dev, r
+        torch.cuda.empty_cache()
+    naive = [0.0] * 8          # arrival order, round robin: the unbalanced baseline
+    for i, L in enumerate(pool):
+        naive[i % 8] += a * L * L + b * L
+    report["greedy_demo"] = {"n_sequences": len(pool), "modelled_load_ms": load, "measured_ms": measured,
+                             "wir_modelled": K.knap_wir(load, [1] * 8), "wir_measured": max(measured) / min(measured),
+                             "wir_round_robin_modelled": max(naive) / min(naive)}
+    log(f"[fit] greedy demo: WIR modelled {report['greedy_demo']['wir_modelled']:.3f}, measured "
+        f"{report['greedy_demo']['wir_measured']:.3f}, round-robin (modelled) {report['greedy_demo']['wir_round_robin_modelled']:.3f}")
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     path = os.path.join(ROOT, "gpurun_out", "fit_report.json")
     with open(path, "w") as f:
@@ -309,6 +360,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the step; --gpus must be 1 "
