@@ -51,7 +51,7 @@ extern "C" {
  * rows < T; inputs are never modified; outputs must not alias inputs.
  *
  * Supported: d in {64, 128}; 0 <= n_seq <= KNAP_MAX_SEQS; H >= 1; scale positive
- * and finite; one sequence may span at most 2^31 - 1 bytes of a tensor (L * H * d * 2).
+ * and finite; T < 2^31.
  * n_seq == 0 succeeds and enqueues nothing.
  * ------------------------------------------------------------------------ */
 
