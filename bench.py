@@ -38,6 +38,7 @@ class HipEvents:
     """hipEvent_t pairs from the HIP runtime PyTorch already loaded (RTLD_NOLOAD: never a second runtime)."""
 
     def __init__(self):
+        import torch  # noqa: F401  (brings its HIP runtime into the process; RTLD_NOLOAD then finds it)
         self.hip = C.CDLL("libamdhip64.so.7", mode=os.RTLD_NOLOAD | C.RTLD_GLOBAL)
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]

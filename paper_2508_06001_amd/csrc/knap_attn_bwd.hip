@@ -16,13 +16,10 @@
 // dP: seven contractions are issued for the five the mathematics needs, nothing
 // is reduced across workgroups, and the result is bitwise reproducible.
 //
-// dK/dV kernel: a persistent workgroup (4 waves) owns a 128-row key/value tile of
-// one (sequence, head) and walks over that sequence's queries 64 rows at a time.
-// Wave w owns key columns [32 w, 32 w + 32): its K and V rows stay in registers
-// as MFMA B operands.  With S = Q K^T in the MFMA result layout a lane holds one
-// key column and its registers run over queries, so P and dS are, unchanged, the
-// A operands of dV += P^T dO and dK += dS^T Q; dO and Q enter those as B operands
-// through transposing LDS reads of the row-major tiles.
+// dK/dV kernel: a persistent workgroup of 8 waves owns a 128-row key/value tile of one (sequence,
+// head) and walks over that sequence's queries 64 rows at a time; wave pairs split the work by
+// output (one wave S, P, dV; its partner dP, dS, dK, one tile behind) so that each wave holds a
+// single accumulator and two waves fit on a SIMD.  Details at the kernel.
 //
 // dQ kernel: the forward kernel's structure.  S^T = K Q^T and dP^T = V dO^T put
 // one query in each lane, LSE and delta are per-lane scalars, and dS^T is,
@@ -34,11 +31,13 @@ namespace knap {
 
 template <int D>
 struct BwdCfg {
+  static constexpr int THREADS = 512;      // 8 waves: 4 key blocks x 2 roles
   static constexpr int BM = 64;            // query rows per step
   static constexpr int BN = 128;           // key/value rows per workgroup
   static constexpr int MB = BM / 32;
   static constexpr int NB = D / 32;
   static constexpr int KC = D / 16;
+  static constexpr int NBUF = 3;           // ring of query-side tiles: being loaded / dV role / dK role
   static constexpr int TILE_ELEMS = BM * Tile<D>::LD;   // Q / dO tiles: read both row-wise and transposed
 };
 
@@ -68,8 +67,21 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_prep_kernel(
   }
 }
 
+// dK/dV kernel.  A workgroup of 8 waves owns a 128-row key/value tile of one (sequence, head) and
+// walks over that sequence's queries 64 rows at a time.  The waves form 4 pairs, pair i owning key
+// rows [32 i, 32 i + 32); the two waves of a pair (placed on the same SIMD) split the work by output:
+//   dV wave: keeps its K rows in registers, S = Q K^T, P = exp2(c S - LSE2), dV += P^T dO, and hands
+//            the packed bf16 P to its partner through LDS;
+//   dK wave: keeps its V rows in registers and runs ONE TILE BEHIND: dP = dO V^T, dS = P (dP - delta)
+//            with the partner's P, dK += dS^T Q.
+// Each wave holds one 32 x d fp32 accumulator, so two waves fit on a SIMD and each one's MFMAs run
+// against the other's exponentials, LDS reads and waits.  With S = Q K^T in the MFMA result layout a
+// lane holds one key and its registers run over queries, so P and dS are, unchanged, the A operands
+// of the second products; dO and Q enter those through transposing LDS reads.  The exchange is one
+// way (dV wave -> dK wave, double buffered) and the query-side tiles live in a ring of three
+// buffers, so one workgroup barrier per tile covers every hand-over.
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
+__global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
     const int32_t* __restrict__ cu, int n_seq, int H, float scale,
@@ -78,31 +90,33 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
   extern __shared__ int s_dyn[];
   int* s_order = s_dyn;
   int* s_start = s_dyn + n_seq;
-  __shared__ int s_part[kThreads];
-  // two copies of the query-side tiles: the next step's tile lands while this one is used
-  __shared__ __attribute__((aligned(16))) __bf16 sQ[2][C::TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) __bf16 sdO[2][C::TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) float sLse[2][C::BM];     // LSE in base 2; +inf for rows past the end
-  __shared__ __attribute__((aligned(16))) float sDelta[2][C::BM];
+  __shared__ __attribute__((aligned(16))) __bf16 sQ[C::NBUF][C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 sdO[C::NBUF][C::TILE_ELEMS];
+  __shared__ __attribute__((aligned(16))) float sLse[C::NBUF][C::BM];     // LSE in base 2; +inf for rows past the end
+  __shared__ __attribute__((aligned(16))) float sDelta[C::NBUF][C::BM];
+  __shared__ __attribute__((aligned(16))) u32x4 sP[4][2][2 * C::MB][64];  // [pair][parity][chunk of 16 queries][lane]
+  static_assert(sizeof(sP) >= sizeof(int) * C::THREADS, "scan scratch must fit in the exchange buffer");
 
-  const int n_items = build_schedule<C::BN>(cu, n_seq, H, s_order, s_start, s_part);
+  const int n_items = build_schedule<C::BN, C::THREADS>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int pair = wave & 3;        // key block; waves w and w + 4 share a SIMD
+  const int role = wave >> 2;       // 0: dV wave, 1: dK wave
   const int l32 = lane & 31;
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
   const size_t row_stride = (size_t)H * D;
   const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
 
-  constexpr int TPR = D / 8;
-  constexpr int RPP = kThreads / TPR;
-  constexpr int NP = C::BM / RPP;            // 16-byte loads per thread and tensor per tile
+  constexpr int TPR = D / 8;                         // 16-byte chunks per row
+  constexpr int RPP = C::THREADS / TPR;              // rows per pass
+  constexpr int NP = C::BM / RPP;                    // 16-byte loads per thread and tensor per tile
   const int ld_row = tid / TPR;
   const int ld_col = (tid % TPR) * 8;
-  RowReader<D> rows;     // Q and dO tile rows -> A operands of S and dP
-  ColReader<D> cols;     // dO and Q tile columns -> B operands of dV += P^T dO and dK += dS^T Q
+  RowReader<D> rows;     // Q / dO tile rows -> A operands of S / dP
+  ColReader<D> cols;     // dO / Q tile columns -> B operands of dV += P^T dO / dK += dS^T Q
   rows.init(lane);
   cols.init(lane);
 
@@ -116,186 +130,177 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkdv_kernel(
     const float* lse_base = lse + (size_t)it.head * T + it.row0;
     const float* delta_base = delta + (size_t)it.head * T + it.row0;
 
-    // this wave's key rows as B operands of S = Q K^T and dP = dO V^T (rows past the end read as zero)
-    bf16x8 kf[C::KC], vf[C::KC];
+    // this wave's 32 key rows of K (dV wave) or V (dK wave) as B operands; rows past the end read as zero
+    bf16x8 kvf[C::KC];
     {
       const uint32_t kv_bytes = (uint32_t)min(L - kv0, C::BN) * row_bytes;
-      const auto rk = make_rsrc(k + (size_t)(it.row0 + kv0) * row_stride + head_off, kv_bytes);
-      const auto rv = make_rsrc(v + (size_t)(it.row0 + kv0) * row_stride + head_off, kv_bytes);
-      const uint32_t off = (uint32_t)(32 * wave + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
+      const __bf16* src = (role == 0 ? k : v) + (size_t)(it.row0 + kv0) * row_stride + head_off;
+      const auto r = make_rsrc(src, kv_bytes);
+      const uint32_t off = (uint32_t)(32 * pair + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
 #pragma unroll
-      for (int cc = 0; cc < C::KC; ++cc) {
-        kf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rk, off + 32u * cc));
-        vf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rv, off + 32u * cc));
-      }
+      for (int cc = 0; cc < C::KC; ++cc) kvf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(r, off + 32u * cc));
     }
 
-    f32x16 dk_acc[C::NB], dv_acc[C::NB];
+    f32x16 acc[C::NB];     // dV (dV wave) or dK (dK wave) rows of this pair
 #pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb) { dk_acc[nb] = zero16(); dv_acc[nb] = zero16(); }
+    for (int nb = 0; nb < C::NB; ++nb) acc[nb] = zero16();
 
     const int n_tiles = (L + C::BM - 1) / C::BM;
-    u32x4 gq[NP], gd[NP];
-    float g_lse = 0.f, g_delta = 0.f;
 
-    // global -> registers; a tile past the end of the sequence reads as zeros (LSE +inf)
-    auto fetch_tile = [&](int t) {
+    // A query-side tile travels global -> registers -> LDS.  Under load a tile's loads take longer
+    // than one step's arithmetic, so TWO tiles are kept in flight: tile t + 2 is requested at the
+    // top of step t into one register set while tile t + 1, requested a step earlier into the
+    // other set, is written to LDS at the bottom of step t.
+    struct Staged {
+      u32x4 q[NP], d[NP];
+      float lse, delta;
+      bool ok;
+    };
+    Staged stA, stB;       // tiles of even / odd index
+
+    // nothing here may wait for a load: the data is first touched in commit_tile
+    auto fetch_tile = [&](int t, Staged& st) {
       const int q0 = t * C::BM;
-      const uint32_t bytes = (uint32_t)max(0, min(L - q0, C::BM)) * row_bytes;
+      const uint32_t bytes = (uint32_t)max(0, min(L - q0, C::BM)) * row_bytes;   // past the end: zeros
       const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, bytes);
       const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, bytes);
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         const uint32_t off = (uint32_t)(p * RPP + ld_row) * row_bytes + (uint32_t)ld_col * 2u;
-        gq[p] = buffer_load16(rq, off);
-        gd[p] = buffer_load16(rd, off);
+        st.q[p] = buffer_load16(rq, off);
+        st.d[p] = buffer_load16(rd, off);
       }
-      const int r = tid & (C::BM - 1);          // every row is fetched by kThreads / BM threads
-      const bool ok = q0 + r < L;
-      const int qi = ok ? q0 + r : 0;
-      const float a = lse_base[qi], b = delta_base[qi];
-      g_lse = ok ? a * kLog2e : INFINITY;       // +inf makes P = 0 on rows past the end
-      g_delta = ok ? b : 0.f;
+      const int r = tid & (C::BM - 1);          // every row is fetched by THREADS / BM threads
+      st.ok = q0 + r < L;
+      const int qi = st.ok ? q0 + r : 0;
+      st.lse = lse_base[qi];
+      st.delta = delta_base[qi];
     };
-    auto commit_tile = [&](int buf) {           // registers -> LDS
+    auto commit_tile = [&](int buf, const Staged& st) {      // registers -> LDS
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         const int o_ = Tile<D>::off(p * RPP + ld_row, ld_col);
-        *reinterpret_cast<u32x4*>(&sQ[buf][o_]) = gq[p];
-        *reinterpret_cast<u32x4*>(&sdO[buf][o_]) = gd[p];
+        *reinterpret_cast<u32x4*>(&sQ[buf][o_]) = st.q[p];
+        *reinterpret_cast<u32x4*>(&sdO[buf][o_]) = st.d[p];
       }
-      sLse[buf][tid & (C::BM - 1)] = g_lse;
-      sDelta[buf][tid & (C::BM - 1)] = g_delta;
+      sLse[buf][tid & (C::BM - 1)] = st.ok ? st.lse * kLog2e : INFINITY;   // +inf makes P = 0 on rows past the end
+      sDelta[buf][tid & (C::BM - 1)] = st.ok ? st.delta : 0.f;
     };
 
-    __syncthreads();       // the previous item is done with both buffers
-    fetch_tile(0);
-    commit_tile(0);
-    __syncthreads();
-
-    for (int t = 0; t < n_tiles; ++t) {
-      const int cur = t & 1;
-      fetch_tile(t + 1);
-      const __bf16* tQ = sQ[cur];
-      const __bf16* tdO = sdO[cur];
-      const float* tLse = sLse[cur];
-      const float* tDelta = sDelta[cur];
-
-      // The 64-query tile is processed as two halves of 32 queries.  With one wave per SIMD
-      // nothing overlaps unless it is interleaved in program order, so the halves form a
-      // static software pipeline of four slots; in each slot one MFMA group runs against
-      // the LDS reads or the softmax arithmetic of the other half:
-      //   slot 1: S, dP of half 0          | row fragments of half 1
-      //   slot 2: S, dP of half 1          | P, dS of half 0, transposed fragments of half 0
-      //   slot 3: dV, dK += half 0         | P, dS of half 1, transposed fragments of half 1
-      //   slot 4: dV, dK += half 1         | next tile: registers -> LDS
-      auto read_rows = [&](int mb, bf16x8 (&aq)[C::KC], bf16x8 (&ad)[C::KC]) {
+    // dV wave, tile t in buffer b: S, P, hand P over, dV += P^T dO
+    auto dv_step = [&](int t, int b) {
+      const __bf16* tQ = sQ[b];
+      const __bf16* tdO = sdO[b];
+      f32x16 s[C::MB];
 #pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) {
-          aq[cc] = rows.get(tQ, 32 * mb, cc);
-          ad[cc] = rows.get(tdO, 32 * mb, cc);
-        }
-      };
-      auto read_transposed = [&](int mb, bf16x8 (&bo)[2][C::NB], bf16x8 (&bq)[2][C::NB]) {
+      for (int mb = 0; mb < C::MB; ++mb) {
+        s[mb] = zero16();
 #pragma unroll
-        for (int cq = 0; cq < 2; ++cq)
+        for (int cc = 0; cc < C::KC; ++cc) s[mb] = mfma32(rows.get(tQ, 32 * mb, cc), kvf[cc], s[mb]);
+      }
+      KNAP_STREAM_READS(C::MB * C::KC, 1, 4);
+      KNAP_SCHED_FENCE();
+      // P = exp2(c S - LSE2); register r of block mb is query 32 mb + 8 (r / 4) + 4 hh + r % 4; packed so
+      // that element e of chunk cq is query 16 cq + 8 (e / 4) + 4 hh + e % 4
+      bf16x8 pa[2 * C::MB];
 #pragma unroll
-          for (int nb = 0; nb < C::NB; ++nb) {
-            bo[cq][nb] = cols.get(tdO, 32 * mb + 16 * cq, nb);
-            bq[cq][nb] = cols.get(tQ, 32 * mb + 16 * cq, nb);
-          }
-      };
-      auto scores = [&](const bf16x8 (&aq)[C::KC], const bf16x8 (&ad)[C::KC], f32x16& s, f32x16& dp) {
-        s = zero16();
-        dp = zero16();
-#pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) {
-          s = mfma32(aq[cc], kf[cc], s);
-          dp = mfma32(ad[cc], vf[cc], dp);
-        }
-      };
-      // P = exp2(c S - LSE2), dS = P (dP - delta); register r is query 32 mb + 8 (r / 4) + 4 hh + r % 4.
-      // Packed so that element e of chunk cq is query 32 mb + 16 cq + 8 (e / 4) + 4 hh + e % 4.
-      auto softmax_math = [&](int mb, const f32x16& s, const f32x16& dp, bf16x8 (&pa)[2], bf16x8 (&da)[2]) {
-        float p[16], ds[16];
+      for (int mb = 0; mb < C::MB; ++mb) {
+        float p[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int qi = 32 * mb + 8 * g + 4 * hh;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&tLse[qi]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&tDelta[qi]);
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[b][32 * mb + 8 * g + 4 * hh]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) p[4 * g + e] = fast_exp2(__builtin_fmaf(s[mb][4 * g + e], c, -l4[e]));
+        }
+        pa[2 * mb] = pack8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
+        pa[2 * mb + 1] = pack8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
+      }
+#pragma unroll
+      for (int cq = 0; cq < 2 * C::MB; ++cq) sP[pair][t & 1][cq][lane] = __builtin_bit_cast(u32x4, pa[cq]);
+      KNAP_SCHED_FENCE();
+#pragma unroll
+      for (int cq = 0; cq < 2 * C::MB; ++cq)
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) acc[nb] = mfma32(pa[cq], cols.get(tdO, 16 * cq, nb), acc[nb]);
+      KNAP_STREAM_READS(2 * C::MB * C::NB, 2, 3);
+      KNAP_SCHED_FENCE();
+    };
+    // dK wave, tile u in buffer b: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
+    auto dk_step = [&](int u, int b) {
+      const __bf16* tQ = sQ[b];
+      const __bf16* tdO = sdO[b];
+      f32x16 dp[C::MB];
+#pragma unroll
+      for (int mb = 0; mb < C::MB; ++mb) {
+        dp[mb] = zero16();
+#pragma unroll
+        for (int cc = 0; cc < C::KC; ++cc) dp[mb] = mfma32(rows.get(tdO, 32 * mb, cc), kvf[cc], dp[mb]);
+      }
+      u32x4 pw[2 * C::MB];
+#pragma unroll
+      for (int cq = 0; cq < 2 * C::MB; ++cq) pw[cq] = sP[pair][u & 1][cq][lane];
+      KNAP_STREAM_READS(C::MB * C::KC, 1, 4);
+      KNAP_SCHED_FENCE();
+      bf16x8 da[2 * C::MB];
+#pragma unroll
+      for (int mb = 0; mb < C::MB; ++mb) {
+        float ds[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDelta[b][32 * mb + 8 * g + 4 * hh]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            p[4 * g + e] = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
-            ds[4 * g + e] = p[4 * g + e] * (dp[4 * g + e] - d4[e]);
+            const int r = 4 * g + e;                       // register r <-> element r % 8 of chunk 2 mb + r / 8
+            const uint32_t word = pw[2 * mb + (r >> 3)][(r & 7) >> 1];
+            const float p = __builtin_bit_cast(float, (r & 1) ? (word & 0xffff0000u) : (word << 16));
+            ds[r] = p * (dp[mb][r] - d4[e]);
           }
         }
+        da[2 * mb] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+        da[2 * mb + 1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+      }
+      KNAP_SCHED_FENCE();
 #pragma unroll
-        for (int cq = 0; cq < 2; ++cq) {
-          const int r0 = 8 * cq;
-          pa[cq] = pack8(p[r0], p[r0 + 1], p[r0 + 2], p[r0 + 3], p[r0 + 4], p[r0 + 5], p[r0 + 6], p[r0 + 7]);
-          da[cq] = pack8(ds[r0], ds[r0 + 1], ds[r0 + 2], ds[r0 + 3], ds[r0 + 4], ds[r0 + 5], ds[r0 + 6], ds[r0 + 7]);
-        }
-      };
-      auto accumulate = [&](const bf16x8 (&pa)[2], const bf16x8 (&da)[2],
-                            const bf16x8 (&bo)[2][C::NB], const bf16x8 (&bq)[2][C::NB]) {
+      for (int cq = 0; cq < 2 * C::MB; ++cq)
 #pragma unroll
-        for (int cq = 0; cq < 2; ++cq)
-#pragma unroll
-          for (int nb = 0; nb < C::NB; ++nb) {
-            dv_acc[nb] = mfma32(pa[cq], bo[cq][nb], dv_acc[nb]);
-            dk_acc[nb] = mfma32(da[cq], bq[cq][nb], dk_acc[nb]);
-          }
-      };
-      constexpr int NM_A = 2 * C::KC;        // MFMAs of one S, dP group
-      constexpr int NM_C = 4 * C::NB;        // MFMAs of one dV, dK group
+        for (int nb = 0; nb < C::NB; ++nb) acc[nb] = mfma32(da[cq], cols.get(tQ, 16 * cq, nb), acc[nb]);
+      KNAP_STREAM_READS(2 * C::MB * C::NB, 2, 3);
+      KNAP_SCHED_FENCE();
+    };
 
-      bf16x8 aq0[C::KC], ad0[C::KC], aq1[C::KC], ad1[C::KC];
-      bf16x8 bo0[2][C::NB], bq0[2][C::NB], bo1[2][C::NB], bq1[2][C::NB];
-      bf16x8 pa0[2], da0[2], pa1[2], da1[2];
-      f32x16 s0, dp0, s1, dp1;
+    __syncthreads();       // the previous item (or the schedule build) is done with every buffer
+    fetch_tile(0, stA);
+    commit_tile(0, stA);
+    if (n_tiles > 1) fetch_tile(1, stB);
+    __syncthreads();
 
-      read_rows(0, aq0, ad0);
-      KNAP_SCHED_FENCE();
-      // slot 1
-      scores(aq0, ad0, s0, dp0);
-      read_rows(1, aq1, ad1);
-#pragma unroll
-      for (int i = 0; i < NM_A; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 1); }
-      KNAP_SCHED_FENCE();
-      // slot 2
-      scores(aq1, ad1, s1, dp1);
-      softmax_math(0, s0, dp0, pa0, da0);
-      read_transposed(0, bo0, bq0);
-#pragma unroll
-      for (int i = 0; i < NM_A; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 3); KNAP_SGB(KNAP_SG_VALU, 7); }
-      KNAP_SCHED_FENCE();
-      // slot 3
-      accumulate(pa0, da0, bo0, bq0);
-      softmax_math(1, s1, dp1, pa1, da1);
-      read_transposed(1, bo1, bq1);
-#pragma unroll
-      for (int i = 0; i < NM_C; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_READ, 3); KNAP_SGB(KNAP_SG_VALU, 7); }
-      KNAP_SCHED_FENCE();
-      // slot 4
-      accumulate(pa1, da1, bo1, bq1);
-      commit_tile(cur ^ 1);
-#pragma unroll
-      for (int i = 0; i < NM_C; ++i) { KNAP_SGB(KNAP_SG_MFMA, 1); KNAP_SGB(KNAP_SG_DS_WRITE, 1); }
-      KNAP_SCHED_FENCE();
-      __syncthreads();     // next tile visible; this tile no longer read
+    // step t: the dV wave works on tile t, the dK wave on tile t - 1, tile t + 1 sits in registers
+    // (`staged`) and tile t + 2 is requested (`incoming`)
+    auto step = [&](int t, Staged& incoming, const Staged& staged) {
+      if (t + 2 < n_tiles) fetch_tile(t + 2, incoming);
+      if (role == 0) {
+        if (t < n_tiles) dv_step(t, t % C::NBUF);
+      } else {
+        if (t >= 1) dk_step(t - 1, (t - 1) % C::NBUF);
+      }
+      if (t + 1 < n_tiles) commit_tile((t + 1) % C::NBUF, staged);
+      __syncthreads();     // P of tile t and tile t + 1 visible; tile t - 1 and P of tile t - 1 released
+    };
+    for (int t = 0; t <= n_tiles; t += 2) {
+      step(t, stA, stB);
+      if (t + 1 <= n_tiles) step(t + 1, stB, stA);
     }
 
-    // dK (scaled) and dV rows of this wave: register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
+    // this wave's rows of dV, or of dK (scaled): register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
+    __bf16* dst = role == 0 ? dv : dk;
+    const float out_scale = role == 0 ? 1.0f : scale;
 #pragma unroll
     for (int nb = 0; nb < C::NB; ++nb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int kv = kv0 + 32 * wave + 8 * (r >> 2) + 4 * hh + (r & 3);
-        if (kv < L) {
-          const size_t g = (size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32;
-          dk[g] = (__bf16)(dk_acc[nb][r] * scale);
-          dv[g] = (__bf16)dv_acc[nb][r];
-        }
+        const int kv = kv0 + 32 * pair + 8 * (r >> 2) + 4 * hh + (r & 3);
+        if (kv < L)
+          dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[nb][r] * out_scale);
       }
   }
 }
@@ -403,8 +408,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         bf16x8 kt0[C::DB];
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) kt0[db] = cols.get(tK, 32 * half, db);
-#pragma unroll
-        for (int i = 0; i < 2 * C::KC; ++i) { KNAP_SGB(KNAP_SG_DS_READ, 1); KNAP_SGB(KNAP_SG_MFMA, 1); }
+        KNAP_STREAM_READS(2 * C::KC, 1, 4);
         KNAP_SCHED_FENCE();
         // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2); element e of chunk ck is key
         // 32 half + 16 ck + 8 (e / 4) + 4 hh + e % 4
@@ -418,6 +422,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         for (int db = 0; db < C::DB; ++db) acc[db] = mfma32(kt0[db], d0, acc[db]);
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) acc[db] = mfma32(cols.get(tK, 32 * half + 16, db), d1, acc[db]);
+        KNAP_SGB(KNAP_SG_DS_READ, 2 * C::DB);          // the second chunk's K^T fragments go out first
+        KNAP_SGB(KNAP_SG_MFMA, 2 * C::DB);
         KNAP_SCHED_FENCE();
       }
       wait_async_loads();
@@ -459,7 +465,7 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
   if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<D>, dim3(grid_dkdv), dim3(kThreads), dyn, stream,
+  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<D>, dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
                      (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
   e = hipGetLastError();
@@ -483,9 +489,9 @@ hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t
                            grid_dkdv, grid_dq, aux_grid, stream, ev_start, ev_stop);
 }
 
-static int occupancy_of(const void* fn) {
+static int occupancy_of(const void* fn, int threads = kThreads) {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, kThreads, 0) != hipSuccess || n < 1) {
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, threads, 0) != hipSuccess || n < 1) {
     (void)hipGetLastError();
     n = 1;
   }
@@ -493,7 +499,8 @@ static int occupancy_of(const void* fn) {
 }
 
 int bwd_dkdv_workgroups_per_cu(int d) {
-  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64> : (const void*)attn_bwd_dkdv_kernel<128>);
+  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64> : (const void*)attn_bwd_dkdv_kernel<128>,
+                      BwdCfg<128>::THREADS);
 }
 
 int bwd_dq_workgroups_per_cu(int d) {

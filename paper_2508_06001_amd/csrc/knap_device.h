@@ -189,6 +189,16 @@ __device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
 #else
 #define KNAP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 #endif
+// Interleave n_mfma MFMAs with the LDS reads that feed them (reads_per_mfma each), keeping the
+// reads `ahead` MFMAs in front of their use so that no MFMA waits out a full LDS latency.
+#define KNAP_STREAM_READS(n_mfma, reads_per_mfma, ahead)                          \
+  do {                                                                            \
+    KNAP_SGB(KNAP_SG_DS_READ, (reads_per_mfma) * (ahead));                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < (n_mfma); ++i_) {                     \
+      KNAP_SGB(KNAP_SG_MFMA, 1);                                                  \
+      KNAP_SGB(KNAP_SG_DS_READ, (reads_per_mfma));                                \
+    }                                                                             \
+  } while (0)
 #define KNAP_SG_VALU 0x002
 #define KNAP_SG_MFMA 0x008
 #define KNAP_SG_DS_READ 0x100
@@ -260,9 +270,10 @@ struct WorkItem {
   int tile;
 };
 
-template <int TILE>
+template <int TILE, int NT = kThreads>
 __device__ __forceinline__ int build_schedule(const int32_t* __restrict__ cu, int n_seq, int H,
-                                              int* s_order, int* s_start, int* s_part /* kThreads ints */) {
+                                              int* s_order, int* s_start, int* s_part /* NT ints */) {
+  constexpr int kThreads = NT;   // threads of the calling workgroup
   const int tid = threadIdx.x;
   for (int i = tid; i < n_seq; i += kThreads) s_start[i] = cu[i + 1] - cu[i];
   __syncthreads();
