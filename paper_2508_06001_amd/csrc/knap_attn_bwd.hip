@@ -271,24 +271,24 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     __syncthreads();       // the previous item (or the schedule build) is done with every buffer
     fetch_tile(0, stA);
     commit_tile(0, stA);
-    if (n_tiles > 1) fetch_tile(1, stB);
+    fetch_tile(1, stB);
     __syncthreads();
 
     // step t: the dV wave works on tile t, the dK wave on tile t - 1, tile t + 1 sits in registers
     // (`staged`) and tile t + 2 is requested (`incoming`)
     auto step = [&](int t, Staged& incoming, const Staged& staged) {
-      if (t + 2 < n_tiles) fetch_tile(t + 2, incoming);
+      fetch_tile(t + 2, incoming);         // past the end: an empty descriptor, every lane reads zero
       if (role == 0) {
         if (t < n_tiles) dv_step(t, t % C::NBUF);
       } else {
-        if (t >= 1) dk_step(t - 1, (t - 1) % C::NBUF);
+        if (t >= 1 && t <= n_tiles) dk_step(t - 1, (t - 1) % C::NBUF);
       }
-      if (t + 1 < n_tiles) commit_tile((t + 1) % C::NBUF, staged);
+      commit_tile((t + 1) % C::NBUF, staged);   // that buffer is free at step t, also when tile t + 1 is past the end
       __syncthreads();     // P of tile t and tile t + 1 visible; tile t - 1 and P of tile t - 1 released
     };
     for (int t = 0; t <= n_tiles; t += 2) {
       step(t, stA, stB);
-      if (t + 1 <= n_tiles) step(t + 1, stB, stA);
+      step(t + 1, stB, stA);     // possibly one step past the end: no work, but the load counts stay exact
     }
 
     // this wave's rows of dV, or of dK (scaled): register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
