@@ -122,10 +122,11 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
     attn = K.VarlenAttention(cu_seqlens_of(bag.seq_lens), bag.H, bag.d, bag.scale)
     attn._ensure_bwd_buffers()
     stream = int(torch.cuda.current_stream().cuda_stream)
-    q, k, v, dout = dev["q"], dev["k"], dev["v"], dev["dout"]
-    for _ in range(warmup):
-        attn.forward(q, k, v)
-        attn.backward(q, k, v, dout)
+    sets = dev if isinstance(dev, (list, tuple)) else [dev]   # input sets, used in rotation
+    for i in range(warmup):
+        x = sets[i % len(sets)]
+        attn.forward(x["q"], x["k"], x["v"])
+        attn.backward(x["q"], x["k"], x["v"], x["dout"])
     torch.cuda.synchronize()
 
     n_ev = steps
@@ -137,11 +138,12 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
+        x = sets[i % len(sets)]
         ev.record(e_f0[i], stream)
-        attn.forward(q, k, v)
+        attn.forward(x["q"], x["k"], x["v"])
         ev.record(e_f1[i], stream)
         K.knap_bwd_profile_events(e_m0[i], e_m1[i])
-        attn.backward(q, k, v, dout)
+        attn.backward(x["q"], x["k"], x["v"], x["dout"])
         ev.record(e_b1[i], stream)
     K.knap_bwd_profile_events(None, None)
     torch.cuda.synchronize()
@@ -150,6 +152,7 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
     bwd = [ev.elapsed_ms(e_f1[i], e_b1[i]) for i in range(steps)]
     main = [ev.elapsed_ms(e_m0[i], e_m1[i]) for i in range(steps)]
     span = ev.elapsed_ms(e_f0[0], e_b1[-1])
+    step = [ev.elapsed_ms(e_f0[i], e_b1[i]) for i in range(steps)]
     for lst in (e_f0, e_f1, e_b1, e_m0, e_m1):
         for e in lst:
             ev.destroy(e)
@@ -158,6 +161,8 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
         "gpu_ms_per_step": span / steps,
         "fwd_ms": float(np.mean(fwd)), "bwd_ms": float(np.mean(bwd)), "bwd_main_ms": float(np.mean(main)),
         "fwd_ms_min": float(np.min(fwd)), "bwd_ms_min": float(np.min(bwd)),
+        "fwd_ms_median": float(np.median(fwd)), "bwd_ms_median": float(np.median(bwd)),
+        "step_ms_median": float(np.median(step)), "step_ms_min": float(np.min(step)),
         "attn": attn,
     }
 
@@ -224,6 +229,9 @@ def run_default(args):
         bits, dev = device_inputs(bag)
     else:
         bits, dev = None, device_inputs_fast(bag)
+    # a second input set of the same bag (other values), used in rotation, so that a small bag's
+    # inputs are not simply still sitting in the cache from the previous step
+    dev = [dev, device_inputs_fast(bag, seed=1)]
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -253,6 +261,9 @@ def run_default(args):
         "paper_convention_tflops": round(value * 12.0 / 14.0, 3),
         "fwd_ms": round(r["fwd_ms"], 4), "bwd_ms": round(r["bwd_ms"], 4),
         "fwd_tflops": round(fwd_tflops, 2),
+        "ms_per_step_median": round(r["step_ms_median"], 4), "ms_per_step_min": round(r["step_ms_min"], 4),
+        "fwd_ms_median": round(r["fwd_ms_median"], 4), "bwd_ms_median": round(r["bwd_ms_median"], 4),
+        "input_sets": 2,
         "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel", "achieved": round(bwd_main_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_main_tflops / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_ms": round(r["bwd_main_ms"], 4),
@@ -304,8 +315,19 @@ def run_fit(args):
         evals = []
         cfgs = [1, 2, 3] if H == 24 else [4]
         for ci in cfgs:
-            for so in range(4 if ci != 4 else 1):
-                bag = config_bag(ci, seed_offset=so)
+            # draw 0 is the benchmark bag; config 4 is fixed, its further "draws" are random bags of
+            # power-of-two lengths (8192 .. 131072) filling the same 196608 tokens
+            for so in range(args.fit_draws if ci != 4 else args.fit_draws - 1):
+                if ci == 4 and so > 0:
+                    rng = np.random.default_rng(7000 + so)
+                    lens, left = [], tokens
+                    while left > 0:
+                        L = int(min(left, 8192 << int(rng.integers(0, 5))))
+                        lens.append(L)
+                        left -= L
+                    bag = BagSpec(f"ulysses_random{so}", lens, H=H, d=d, seed=7000 + so)
+                else:
+                    bag = config_bag(ci, seed_offset=so)
                 dev = device_inputs_fast(bag)
                 r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
                 pred = a * bag.sum_l2 + b * bag.total_tokens
@@ -361,6 +383,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
+    ap.add_argument("--fit-draws", type=int, default=12, help="evaluation bags per benchmark configuration in --fit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()

@@ -120,7 +120,10 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
   rows.init(lane);
   cols.init(lane);
 
-  for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
+  const int wg = xcd_major_block_id();
+  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
+    const int w = serpentine_item(round, wg, (int)gridDim.x);
+    if (w >= n_items) continue;
     const WorkItem it = decode_item<C::BN>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
     const int kv0 = it.tile * C::BN;
@@ -347,7 +350,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   rows.init(lane);
   cols.init(lane);
 
-  for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
+  const int wg = xcd_major_block_id();
+  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
+    const int w = serpentine_item(round, wg, (int)gridDim.x);
+    if (w >= n_items) continue;
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
     const int q0 = it.tile * C::BM;

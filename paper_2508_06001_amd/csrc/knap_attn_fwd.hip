@@ -75,7 +75,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   k_rows.init(lane);
   v_cols.init(lane);
 
-  for (int w = xcd_major_block_id(); w < n_items; w += gridDim.x) {
+  const int wg = xcd_major_block_id();
+  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
+    const int w = serpentine_item(round, wg, (int)gridDim.x);
+    if (w >= n_items) continue;
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
     const int q0 = it.tile * C::BM;

@@ -347,4 +347,13 @@ __device__ __forceinline__ int xcd_major_block_id() {
   return (g % 8 == 0) ? (b % 8) * (g / 8) + b / 8 : b;
 }
 
+// Static assignment of the descending-cost item list to G persistent workgroups: in round r
+// workgroup wg takes item r G + wg, in odd rounds r G + (G - 1 - wg).  Dealing the rounds in
+// serpentine order halves the imbalance of plain round-robin (whoever drew the dearest item of
+// one round draws the cheapest of the next) and keeps neighbouring workgroups on neighbouring
+// items.  Items at or past n_items (last round only) do not exist.
+__device__ __forceinline__ int serpentine_item(int r, int wg, int G) {
+  return r * G + ((r & 1) ? G - 1 - wg : wg);
+}
+
 }  // namespace knap

@@ -94,6 +94,12 @@ def test_mixed_res_image_bag_sampled_heads():
     _full_compare(config_bag(1), heads=[0, 11, 23])
 
 
+def test_second_seed_set():
+    """The same checks on another draw of the lengths and of the values: the result is not seed-specific."""
+    _full_compare(config_bag(0, seed_offset=1))
+    _full_compare(config_bag(1, seed_offset=1), heads=[5])
+
+
 def test_empty_bag_and_zero_length_only():
     import torch
     import paper_2508_06001_amd as K
