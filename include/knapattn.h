@@ -70,7 +70,9 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
  * `workspace` is caller-owned device scratch of at least
  * knap_varlen_attn_bwd_workspace_bytes(total_tokens, n_seq, H, d) bytes,
  * 256-byte aligned; its contents on entry are ignored and on return are
- * unspecified. */
+ * unspecified.  It holds the per-row dot products of dout and out and the
+ * counters of the kernels' work queues, so two calls that may run at the same
+ * time (different streams) need a workspace each. */
 int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          const int32_t* cu_seqlens, int n_seq,
                          int H, int d, float scale,

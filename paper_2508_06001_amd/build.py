@@ -23,6 +23,9 @@ C_SOURCES = ["knap_host.c"]
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the work-queue tickets are drawn by one lane and first looked at an item later; the atomic
+    # optimizer would rewrite the draw into a wave reduction that needs its result at once
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wno-unused-command-line-argument",
 ]
 

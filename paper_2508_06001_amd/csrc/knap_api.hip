@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -16,7 +18,10 @@ struct DeviceInfo {
   int fwd_wg[2] = {0, 0};   // workgroups per CU, index 0: d = 64, 1: d = 128
   int dkdv_wg[2] = {0, 0};
   int dq_wg[2] = {0, 0};
+  unsigned* fwd_queue = nullptr;   // this device's copy of the forward work-queue counters
 };
+
+std::atomic<unsigned> g_fwd_launches{0};   // picks the counter set of a forward launch
 
 // per-device launch geometry, filled on first use (occupancy queries do not allocate)
 DeviceInfo* device_info() {
@@ -36,6 +41,8 @@ DeviceInfo* device_info() {
     di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
     di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
     di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
+    di.fwd_queue = knap::fwd_queue_base();
+    if (!di.fwd_queue) return nullptr;
     di.cus = cus;
   }
   return &di;
@@ -72,7 +79,8 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
   DeviceInfo* di = device_info();
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
   const int grid = di->cus * di->fwd_wg[d == 128];
-  const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, grid,
+  unsigned* counters = di->fwd_queue + 8u * (g_fwd_launches.fetch_add(1u) % (unsigned)knap::fwd_queue_slots());
+  const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, counters, grid,
                                         static_cast<hipStream_t>(stream));
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;
@@ -81,7 +89,8 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d) {
   (void)n_seq;
   if (total_tokens <= 0 || H <= 0 || d <= 0) return 0;
-  return round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256);   // delta, fp32 (H, T)
+  // delta, fp32 (H, T), then 256 bytes of work-queue counters
+  return round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256) + 256;
 }
 
 int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
@@ -107,11 +116,12 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
 
   float* delta = static_cast<float*>(workspace);
+  unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
   const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
   const int grid_dq = di->cus * di->dq_wg[d == 128];
   const int aux_grid = di->cus * 8;
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
-                                        total_tokens, delta, grid_dkdv, grid_dq, aux_grid,
+                                        total_tokens, delta, counters, grid_dkdv, grid_dq, aux_grid,
                                         static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;

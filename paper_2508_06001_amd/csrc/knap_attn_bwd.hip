@@ -41,11 +41,15 @@ struct BwdCfg {
   static constexpr int TILE_ELEMS = BM * Tile<D>::LD;   // Q / dO tiles: read both row-wise and transposed
 };
 
+constexpr int kQueueCounters = 8;    // one work-queue counter per XCD for the dQ kernel
+
 // delta[h][t] = sum_c dout[t][h][c] * out[t][h][c]
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_bwd_prep_kernel(
     const __bf16* __restrict__ out, const __bf16* __restrict__ dout, int64_t T, int H,
-    float* __restrict__ delta) {
+    float* __restrict__ delta, unsigned* __restrict__ counters) {
+  // the work queue of the dQ kernel, which follows on the stream, starts at zero
+  if (blockIdx.x == 0 && threadIdx.x < kQueueCounters) counters[threadIdx.x] = 0u;
   constexpr int LPR = D / 8;   // lanes per (token, head) row, 8 elements each
   const int64_t n_rows = T * H;
   const int sub = threadIdx.x % LPR;
@@ -120,6 +124,7 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
   rows.init(lane);
   cols.init(lane);
 
+  // static assignment: measured, the dynamic queue the dQ kernel uses does not pay here
   const int wg = xcd_major_block_id();
   for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
     const int w = serpentine_item(round, wg, (int)gridDim.x);
@@ -322,7 +327,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
     const int32_t* __restrict__ cu, int n_seq, int H, float scale,
-    __bf16* __restrict__ dq) {
+    __bf16* __restrict__ dq, unsigned* __restrict__ counters) {
   using C = DqCfg<D>;
   extern __shared__ int s_dyn[];
   int* s_order = s_dyn;
@@ -350,10 +355,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   rows.init(lane);
   cols.init(lane);
 
-  const int wg = xcd_major_block_id();
-  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
-    const int w = serpentine_item(round, wg, (int)gridDim.x);
-    if (w >= n_items) continue;
+  // Work items come from this XCD's queue.  The ticket for the NEXT item is requested right
+  // after the item's first loads (vector-memory operations complete in issue order: requested
+  // before them, the slow counter update would hold up the whole prologue) and only looked at
+  // when the item is done, so the counter's latency is never waited for.
+  __shared__ int s_ticket;
+  ItemQueue queue;
+  queue.init(counters);
+  if (tid == 0) s_ticket = (int)atomicAdd(queue.ctr, 1u);
+  __syncthreads();
+  for (;;) {
+    const int w = queue.item(__builtin_amdgcn_readfirstlane(s_ticket));
+    if (w >= n_items) break;
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
     const int q0 = it.tile * C::BM;
@@ -439,6 +452,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     __syncthreads();       // the previous item (or the schedule build) is done with both buffers
     load_tile(0, sK0, sV0);
     wait_async_loads();
+    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
+    if (tid == 0) next_ticket = atomicAdd(queue.ctr, 1u);
     __syncthreads();
     for (int t = 0; t < n_tiles; t += 2) {
       process_tile(t, sK0, sV0, sK1, sV1);
@@ -456,17 +471,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
           *reinterpret_cast<bf16x4*>(o_ptr + 32 * db + 8 * g + 4 * hh) = pk;
         }
     }
+    if (tid == 0) s_ticket = (int)next_ticket;   // every wave took its copy of the old ticket many barriers ago
+    __syncthreads();
   }
 }
 
 template <int D>
 static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H,
                                float scale, const void* out, const float* lse, const void* dout,
-                               void* dq, void* dk, void* dv, int64_t T, float* delta,
+                               void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
                                int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
   hipLaunchKernelGGL(attn_bwd_prep_kernel<D>, dim3(aux_grid), dim3(kThreads), 0, stream,
-                     (const __bf16*)out, (const __bf16*)dout, T, H, delta);
+                     (const __bf16*)out, (const __bf16*)dout, T, H, delta, counters);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
@@ -479,19 +496,19 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   if (ev_start && ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, dim3(grid_dq), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
-                     (const float*)delta, cu, n_seq, H, scale, (__bf16*)dq);
+                     (const float*)delta, cu, n_seq, H, scale, (__bf16*)dq, counters);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, int64_t T, float* delta,
+                      void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
                       int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (d == 64)
-    return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta,
+    return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, counters,
                             grid_dkdv, grid_dq, aux_grid, stream, ev_start, ev_stop);
-  return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta,
+  return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, counters,
                            grid_dkdv, grid_dq, aux_grid, stream, ev_start, ev_stop);
 }
 

@@ -40,12 +40,13 @@ struct FwdCfg {
 };
 
 constexpr float kRescaleThreshold = 8.0f;   // base-2 units
+constexpr int kFwdQueueSlots = 256;
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const int32_t* __restrict__ cu, int n_seq, int H, float scale,
-    __bf16* __restrict__ out, float* __restrict__ lse) {
+    __bf16* __restrict__ out, float* __restrict__ lse, unsigned* __restrict__ counters) {
   using C = FwdCfg<D>;
   using TL = Tile<D>;
   extern __shared__ int s_dyn[];
@@ -75,10 +76,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   k_rows.init(lane);
   v_cols.init(lane);
 
-  const int wg = xcd_major_block_id();
-  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
-    const int w = serpentine_item(round, wg, (int)gridDim.x);
-    if (w >= n_items) continue;
+  // Work items come from this XCD's queue.  The ticket for the NEXT item is requested right
+  // after the item's first loads (vector-memory operations complete in issue order: requested
+  // before them, the slow counter update would hold up the whole prologue) and only looked at
+  // when the item is done, so the counter's latency is never waited for.
+  __shared__ int s_ticket;
+  ItemQueue queue;
+  queue.init(counters);
+  if (tid == 0) s_ticket = (int)atomicAdd(queue.ctr, 1u);
+  __syncthreads();
+  for (;;) {
+    const int w = queue.item(__builtin_amdgcn_readfirstlane(s_ticket));
+    if (w >= n_items) break;
     const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
     const int q0 = it.tile * C::BM;
@@ -222,6 +231,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     __syncthreads();       // the previous item (or the schedule build) is done with both buffers
     load_tile(0, sK0, sV0);
     wait_async_loads();
+    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
+    if (tid == 0) next_ticket = atomicAdd(queue.ctr, 1u);
     __syncthreads();
 
     const bool ragged = (L % C::BN) != 0;
@@ -250,23 +261,52 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
         }
       if (hh == 0) lse[(size_t)it.head * T + it.row0 + q_row] = m_ref * scale + __logf(l_tot);
     }
+    if (tid == 0) s_ticket = (int)next_ticket;   // every wave took its copy of the old ticket many barriers ago
+    __syncthreads();
   }
+}
+
+// The forward entry point has no workspace argument, so the counters of its work queue live
+// in the library's device image: kFwdQueueSlots sets of 8 (one per XCD), handed out in rotation
+// by the host and zeroed on the launch stream right before the kernel that uses them.  Two
+// launches share a set only if kFwdQueueSlots other forward launches were enqueued between
+// them while the first was still running.
+static __device__ __align__(256) unsigned g_fwd_queue[kFwdQueueSlots * 8];
+
+__global__ void fwd_queue_reset_kernel(unsigned* __restrict__ counters) {
+  if (threadIdx.x < 8) counters[threadIdx.x] = 0u;
+}
+
+int fwd_queue_slots() { return kFwdQueueSlots; }
+
+unsigned* fwd_queue_base() {
+  unsigned* p = nullptr;
+  if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(g_fwd_queue)) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  return p;
 }
 
 template <int D>
 static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
-                               int H, float scale, void* out, float* lse, int grid, hipStream_t stream) {
+                               int H, float scale, void* out, float* lse, unsigned* counters, int grid,
+                               hipStream_t stream) {
+  hipLaunchKernelGGL(fwd_queue_reset_kernel, dim3(1), dim3(64), 0, stream, counters);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
   hipLaunchKernelGGL(attn_fwd_kernel<D>, dim3(grid), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, cu, n_seq, H, scale,
-                     (__bf16*)out, lse);
+                     (__bf16*)out, lse, counters);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
-                      int H, int d, float scale, void* out, float* lse, int grid, hipStream_t stream) {
-  if (d == 64) return launch_fwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, grid, stream);
-  return launch_fwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, grid, stream);
+                      int H, int d, float scale, void* out, float* lse, unsigned* counters, int grid,
+                      hipStream_t stream) {
+  if (d == 64) return launch_fwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
+  return launch_fwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
 }
 
 int fwd_workgroups_per_cu(int d) {

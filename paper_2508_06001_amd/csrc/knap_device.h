@@ -356,4 +356,25 @@ __device__ __forceinline__ int serpentine_item(int r, int wg, int G) {
   return r * G + ((r & 1) ? G - 1 - wg : wg);
 }
 
+// Dynamic assignment for kernels that are handed zeroed counters (one unsigned per XCD, 8 in
+// all): the descending-cost item list is cut into chunks of G / 8 consecutive items, chunk j
+// belongs to XCD j % 8 (so that the workgroups of an XCD keep meeting on the same K and V in its
+// L2, and every XCD gets every eighth chunk of every cost band), and the workgroups of an XCD
+// draw that XCD's items in order from its counter: list scheduling, longest first, within the
+// XCD.  A ticket is the value the counter returned; the item of a ticket grows with the ticket,
+// so the first ticket whose item is at or past n_items ends the workgroup.
+struct ItemQueue {
+  unsigned* ctr;
+  int q, n_q, chunk;
+  __device__ __forceinline__ void init(unsigned* counters) {
+    n_q = (gridDim.x % 8 == 0) ? 8 : 1;
+    q = (int)(blockIdx.x % n_q);                  // workgroups go to the XCDs round-robin
+    chunk = max(1, (int)gridDim.x / n_q);
+    ctr = counters + q;
+  }
+  __device__ __forceinline__ int item(int ticket) const {
+    return ((ticket / chunk) * n_q + q) * chunk + ticket % chunk;
+  }
+};
+
 }  // namespace knap

@@ -7,11 +7,17 @@
 namespace knap {
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
-                      int H, int d, float scale, void* out, float* lse, int grid, hipStream_t stream);
+                      int H, int d, float scale, void* out, float* lse, unsigned* counters, int grid,
+                      hipStream_t stream);
+
+// Device address (on the current device) of the forward kernel's work-queue counters:
+// fwd_queue_slots() sets of 8, one set per launch in flight; nullptr on failure.
+unsigned* fwd_queue_base();
+int fwd_queue_slots();
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, int64_t T, float* delta,
+                      void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
                       int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop);
 

@@ -134,6 +134,36 @@ def test_repeatable_and_inputs_untouched():
     assert torch.equal(q0, run.dev["q"])
 
 
+def test_two_streams_at_once_match_one_after_the_other():
+    """Calls that overlap on two streams (each with its own outputs and workspace) do not disturb each
+    other: the work queues they draw from are per launch.  Bitwise equality with the sequential run."""
+    import torch
+    from paper_2508_06001_amd.runtime import bf16_device_to_bits
+    rng = np.random.default_rng(5)
+    bags = [BagSpec("stream_a", [int(x) for x in rng.integers(100, 3000, size=9)], H=4, d=128, seed=811),
+            BagSpec("stream_b", [int(x) for x in rng.integers(50, 1500, size=14)], H=6, d=64, seed=812)]
+    runs = [GpuRun(b) for b in bags]                      # sequential reference (default stream)
+    ref = [[r.out_bits.copy(), r.dq_bits.copy(), r.dk_bits.copy(), r.dv_bits.copy(), r.lse.copy()] for r in runs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]  # default priority
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for r in runs:
+            for t in (r.attn.out, r.attn.dq, r.attn.dk, r.attn.dv):
+                t.fill_(float("nan"))
+            r.attn.lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for r, st in zip(runs, streams):
+            r.attn.forward(r.dev["q"], r.dev["k"], r.dev["v"], stream=st)
+        for r, st in zip(runs, streams):
+            r.attn.backward(r.dev["q"], r.dev["k"], r.dev["v"], r.dev["dout"], stream=st)
+        torch.cuda.synchronize()
+        for r, want in zip(runs, ref):
+            got = [bf16_device_to_bits(r.attn.out), bf16_device_to_bits(r.attn.dq), bf16_device_to_bits(r.attn.dk),
+                   bf16_device_to_bits(r.attn.dv), r.attn.lse.cpu().numpy().astype(np.float64)]
+            for g, w_, name in zip(got, want, ("out", "dq", "dk", "dv", "lse")):
+                assert np.array_equal(g, w_), (rep, r.bag.name, name)
+
+
 # ---------------------------------------------------------------------------
 # Full-size benchmark bags: the oracle evaluates sampled outputs exactly
 # (query rows -> out, lse, dq; key rows -> dk, dv), plus invariants that hold
