@@ -130,7 +130,7 @@ def test_repeatable_and_inputs_untouched():
     assert np.array_equal(out1, bf16_device_to_bits(run.attn.out))      # forward: bitwise repeatable
     assert np.array_equal(dk1, bf16_device_to_bits(run.attn.dk))
     assert np.array_equal(dv1, bf16_device_to_bits(run.attn.dv))
-    assert np.array_equal(dq1, bf16_device_to_bits(run.attn.dq))        # no atomics anywhere: bitwise too
+    assert np.array_equal(dq1, bf16_device_to_bits(run.attn.dq))        # no floating-point atomics anywhere: bitwise too
     assert torch.equal(q0, run.dev["q"])
 
 
