@@ -164,6 +164,41 @@ def test_two_streams_at_once_match_one_after_the_other():
                 assert np.array_equal(g, w_), (rep, r.bag.name, name)
 
 
+def test_hip_graph_replays_match_eager():
+    """Forward + backward captured into a HIP graph (nothing in the calls allocates, synchronises or
+    records a memset): every replay, with eager launches and synchronisations in between, reproduces
+    the eager results bit for bit."""
+    import torch
+    from paper_2508_06001_amd.runtime import bf16_device_to_bits
+    rng = np.random.default_rng(11)
+    bag = BagSpec("graph", [int(x) for x in rng.integers(64, 2500, size=11)], H=4, d=128, seed=913)
+    run = GpuRun(bag)                                      # eager reference; also warms up the library
+    other = GpuRun(BagSpec("graph_other", [700, 90, 1300], H=2, d=64, seed=914))
+    want = [run.out_bits.copy(), run.dq_bits.copy(), run.dk_bits.copy(), run.dv_bits.copy(), run.lse.copy()]
+    a, d = run.attn, run.dev
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        a.forward(d["q"], d["k"], d["v"])
+        a.backward(d["q"], d["k"], d["v"], d["dout"])
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for t in (a.out, a.dq, a.dk, a.dv):
+            t.fill_(float("nan"))
+        a.lse.fill_(float("nan"))
+        # eager work of the same library between the replays (draws other forward queue slots)
+        other.attn.forward(other.dev["q"], other.dev["k"], other.dev["v"])
+        other.attn.backward(other.dev["q"], other.dev["k"], other.dev["v"], other.dev["dout"])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [bf16_device_to_bits(a.out), bf16_device_to_bits(a.dq), bf16_device_to_bits(a.dk),
+               bf16_device_to_bits(a.dv), a.lse.cpu().numpy().astype(np.float64)]
+        for g, w_, name in zip(got, want, ("out", "dq", "dk", "dv", "lse")):
+            assert np.array_equal(g, w_), (rep, name)
+
+
 # ---------------------------------------------------------------------------
 # Full-size benchmark bags: the oracle evaluates sampled outputs exactly
 # (query rows -> out, lse, dq; key rows -> dk, dv), plus invariants that hold
