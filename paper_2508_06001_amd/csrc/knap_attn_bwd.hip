@@ -294,10 +294,14 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
       commit_tile((t + 1) % C::NBUF, staged);   // that buffer is free at step t, also when tile t + 1 is past the end
       __syncthreads();     // P of tile t and tile t + 1 visible; tile t - 1 and P of tile t - 1 released
     };
-    for (int t = 0; t <= n_tiles; t += 2) {
+    // steps 0 .. n_tiles.  The loop body is two unconditional steps (a step under a condition inside
+    // the loop would make the load counts inexact); an odd step left over is taken after it.
+    int t = 0;
+    for (; t + 1 <= n_tiles; t += 2) {
       step(t, stA, stB);
-      step(t + 1, stB, stA);     // possibly one step past the end: no work, but the load counts stay exact
+      step(t + 1, stB, stA);
     }
+    if (t <= n_tiles) step(t, stA, stB);
 
     // this wave's rows of dV, or of dK (scaled): register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
     __bf16* dst = role == 0 ? dv : dk;
