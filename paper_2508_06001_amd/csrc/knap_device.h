@@ -27,11 +27,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;   // 4 waves per workgroup
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -148,20 +146,6 @@ struct ColReader {
     return join(lds_read_tr(p + off[db][0]), lds_read_tr(p + off[db][1]));
   }
 };
-
-// An 8-element MFMA operand whose contraction index runs down a row-major LDS
-// matrix X[k][n] (stride `ld` elements): element e of the lane with column
-// n = n_base + (l % 32) is X[k_lo + e][n] for e < 4 and X[k_hi + e - 4][n] else.
-// `lane` is the lane id; k_lo / k_hi may depend on hh = lane / 32.
-__device__ __forceinline__ bf16x8 lds_operand_tr(const __bf16* X, int ld, int k_lo, int k_hi,
-                                                 int n_base, int lane) {
-  const int i = lane & 15;
-  const int n0 = n_base + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
-  const int kr = i >> 2;
-  bf16x4 lo = lds_read_tr(X + (k_lo + kr) * ld + n0);
-  bf16x4 hi = lds_read_tr(X + (k_hi + kr) * ld + n0);
-  return join(lo, hi);
-}
 
 // Bounds-checked global loads.  A raw buffer descriptor covers `bytes` bytes from
 // `base`; a 16-byte load at an offset at or past `bytes` returns zeros instead of
