@@ -84,6 +84,15 @@ def test_many_short_sequences():
     _full_compare(bag, strict_fwd=False)
 
 
+def test_maximum_number_of_sequences():
+    """KNAP_MAX_SEQS sequences in one bag: the largest schedule the kernels keep in LDS."""
+    import paper_2508_06001_amd as K
+    rng = np.random.default_rng(2048)
+    lens = [int(x) for x in rng.integers(0, 48, size=K.KNAP_MAX_SEQS)]
+    lens[17] = 700                                   # one sequence that spans several tiles
+    _full_compare(BagSpec("max_seqs", lens, H=2, d=128, seed=4545), strict_fwd=False)
+
+
 def test_peaky_softmax_with_outlier_keys():
     bag = BagSpec("peaky", [700, 333], H=2, d=128, seed=4444, k_outlier_prob=0.01, k_outlier_scale=8.0)
     _full_compare(bag)
