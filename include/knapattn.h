@@ -93,8 +93,8 @@ int knap_last_hip_error(void);
 
 /* Benchmark hook.  While both are non-NULL, every backward call made by this
  * thread records `start` right before and `stop` right after its dK/dV kernel
- * (the longest kernel of the path) on the call's stream; the preprocess and dQ
- * kernels stay outside the pair.  hipEvent_t passed as void*, owned
+ * (the longest kernel of the path) on the call's stream; the dQ kernel, which
+ * runs before it, stays outside the pair.  hipEvent_t passed as void*, owned
  * by the caller.  Pass NULLs to switch it off.  Not for use under graph capture. */
 void knap_bwd_profile_events(void* start, void* stop);
 

@@ -119,9 +119,8 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
   unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
   const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
   const int grid_dq = di->cus * di->dq_wg[d == 128];
-  const int aux_grid = di->cus * 8;
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
-                                        total_tokens, delta, counters, grid_dkdv, grid_dq, aux_grid,
+                                        delta, counters, grid_dkdv, grid_dq,
                                         static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;

@@ -3,10 +3,10 @@
 // the forward's log-sum-exp (the training loop of Sec. 4 backpropagates through
 // the attention of Sec. 3.4; Sec. 4.2 counts the backward as twice the forward).
 //
-//   delta_i = sum_c dO_ic O_ic                        (preprocess kernel)
+//   delta_i = sum_c dO_ic O_ic                        (dQ kernel, which holds the dO rows of its queries anyway)
 //   S = Q K^T, P = exp(scale S - LSE), dP = dO V^T, dS = P (dP - delta)
+//   dQ = scale dS K                                    (dQ kernel, query-tile major; runs first)
 //   dV = P^T dO, dK = scale dS^T Q                     (dK/dV kernel, key-tile major)
-//   dQ = scale dS K                                    (dQ kernel, query-tile major)
 //
 // dQ sums over keys and dK, dV sum over queries.  Doing all three in one pass
 // needs a cross-workgroup reduction of one of them; on MI355X fp32 atomics into
@@ -43,32 +43,9 @@ struct BwdCfg {
 
 constexpr int kQueueCounters = 8;    // one work-queue counter per XCD for the dQ kernel
 
-// delta[h][t] = sum_c dout[t][h][c] * out[t][h][c]
-template <int D>
-__global__ __launch_bounds__(kThreads) void attn_bwd_prep_kernel(
-    const __bf16* __restrict__ out, const __bf16* __restrict__ dout, int64_t T, int H,
-    float* __restrict__ delta, unsigned* __restrict__ counters) {
-  // the work queue of the dQ kernel, which follows on the stream, starts at zero
-  if (blockIdx.x == 0 && threadIdx.x < kQueueCounters) counters[threadIdx.x] = 0u;
-  constexpr int LPR = D / 8;   // lanes per (token, head) row, 8 elements each
-  const int64_t n_rows = T * H;
-  const int sub = threadIdx.x % LPR;
-  for (int64_t row = (int64_t)blockIdx.x * (kThreads / LPR) + threadIdx.x / LPR; row < n_rows;
-       row += (int64_t)gridDim.x * (kThreads / LPR)) {
-    const size_t off = (size_t)row * D + sub * 8;
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(out + off);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + off);
-    float acc = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
-#pragma unroll
-    for (int s = 1; s < LPR; s <<= 1) acc += __shfl_xor(acc, s, 64);
-    if (sub == 0) {
-      const int64_t t = row / H;
-      const int h = (int)(row - t * H);
-      delta[(size_t)h * T + t] = acc;
-    }
-  }
+// the work queue of the dQ kernel, which follows on the stream, starts at zero
+__global__ void bwd_queue_reset_kernel(unsigned* __restrict__ counters) {
+  if (threadIdx.x < kQueueCounters) counters[threadIdx.x] = 0u;
 }
 
 // dK/dV kernel.  A workgroup of 8 waves owns a 128-row key/value tile of one (sequence, head) and
@@ -329,8 +306,8 @@ struct DqCfg {
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-    const __bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
-    const int32_t* __restrict__ cu, int n_seq, int H, float scale,
+    const __bf16* __restrict__ out, const __bf16* __restrict__ dout, const float* __restrict__ lse,
+    float* __restrict__ delta, const int32_t* __restrict__ cu, int n_seq, int H, float scale,
     __bf16* __restrict__ dq, unsigned* __restrict__ counters) {
   using C = DqCfg<D>;
   extern __shared__ int s_dyn[];
@@ -378,25 +355,35 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const bool q_valid = q_row < L;
     const size_t head_off = (size_t)it.head * D;
 
-    // this lane's q and dO rows as B operands (rows past the end read as zero)
+    // this lane's q and dO rows as B operands (rows past the end read as zero), and
+    // delta = sum_c dO_c O_c of its query: the lane holds half of the row's elements (8 of every 16),
+    // its partner at lane ^ 32 the other half.  The dK/dV kernel reads delta from memory afterwards.
     bf16x8 qf[C::KC], dof[C::KC];
+    float dl = 0.f;
     {
       const uint32_t bytes = (uint32_t)min(L - q0, C::BM) * row_bytes;
       const auto rq = make_rsrc(q + (size_t)(it.row0 + q0) * row_stride + head_off, bytes);
       const auto rd = make_rsrc(dout + (size_t)(it.row0 + q0) * row_stride + head_off, bytes);
+      const auto ro = make_rsrc(out + (size_t)(it.row0 + q0) * row_stride + head_off, bytes);
       const uint32_t off = (uint32_t)(wave * 32 + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
+      bf16x8 of[C::KC];
 #pragma unroll
       for (int cc = 0; cc < C::KC; ++cc) {
         qf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rq, off + 32u * cc));
         dof[cc] = __builtin_bit_cast(bf16x8, buffer_load16(rd, off + 32u * cc));
+        of[cc] = __builtin_bit_cast(bf16x8, buffer_load16(ro, off + 32u * cc));
       }
+#pragma unroll
+      for (int cc = 0; cc < C::KC; ++cc)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dl = __builtin_fmaf((float)dof[cc][e], (float)of[cc][e], dl);
+      dl += xor32(dl);
     }
     // per-lane scalars of this lane's query; +inf LSE turns rows past the end into P = 0
     const int q_idx = q_valid ? q_row : 0;
     const float lse_raw = lse[(size_t)it.head * T + it.row0 + q_idx];
-    const float dl_raw = delta[(size_t)it.head * T + it.row0 + q_idx];
     const float lse2 = q_valid ? lse_raw * kLog2e : INFINITY;
-    const float dl = q_valid ? dl_raw : 0.f;
+    if (q_valid && hh == 0) delta[(size_t)it.head * T + it.row0 + q_row] = dl;
 
     f32x16 acc[C::DB];
 #pragma unroll
@@ -483,14 +470,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
 template <int D>
 static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H,
                                float scale, const void* out, const float* lse, const void* dout,
-                               void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
-                               int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
+                               void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                               int grid_dkdv, int grid_dq, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
-  hipLaunchKernelGGL(attn_bwd_prep_kernel<D>, dim3(aux_grid), dim3(kThreads), 0, stream,
-                     (const __bf16*)out, (const __bf16*)dout, T, H, delta, counters);
+  hipLaunchKernelGGL(bwd_queue_reset_kernel, dim3(1), dim3(64), 0, stream, counters);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
+  // the dQ kernel also produces delta, which the dK/dV kernel needs: it goes first
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, dim3(grid_dq), dim3(kThreads), dyn, stream,
+                     (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)out,
+                     (const __bf16*)dout, lse, delta, cu, n_seq, H, scale, (__bf16*)dq, counters);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dkdv_kernel<D>, dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
@@ -498,22 +490,19 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, dim3(grid_dq), dim3(kThreads), dyn, stream,
-                     (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
-                     (const float*)delta, cu, n_seq, H, scale, (__bf16*)dq, counters);
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
-                      int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
+                      void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                      int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (d == 64)
-    return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, counters,
-                            grid_dkdv, grid_dq, aux_grid, stream, ev_start, ev_stop);
-  return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, T, delta, counters,
-                           grid_dkdv, grid_dq, aux_grid, stream, ev_start, ev_stop);
+    return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters,
+                            grid_dkdv, grid_dq, stream, ev_start, ev_stop);
+  return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters,
+                           grid_dkdv, grid_dq, stream, ev_start, ev_stop);
 }
 
 static int occupancy_of(const void* fn, int threads = kThreads) {

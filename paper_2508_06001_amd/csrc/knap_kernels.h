@@ -17,8 +17,8 @@ int fwd_queue_slots();
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, int64_t T, float* delta, unsigned* counters,
-                      int grid_dkdv, int grid_dq, int aux_grid, hipStream_t stream,
+                      void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                      int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // resident workgroups per compute unit of the persistent kernels
