@@ -12,7 +12,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("HIP error %s line %d\n", hipGetErrorString(e), __LINE__); exit(1);} } while (0)
 
-enum Work { NONE = 0, MFMA = 1, FMA = 2, EXP = 3, LDS = 4, MFMA_FMA = 5, MFMA_EXP = 6, MFMA_LDS = 7 };
+enum Work { NONE = 0, MFMA = 1, FMA = 2, EXP = 3, LDS = 4, MFMA_FMA = 5, MFMA_EXP = 6, MFMA_LDS = 7, MIX = 8, MIX_TR = 9 };
 
 // per loop iteration: MFMA: 8 MFMAs (2 accumulators alternating); FMA / EXP: 48 VALU instructions on 16
 // independent chains; LDS: 8 ds_read_b128; the MFMA_x kinds issue both, interleaved by the compiler's
@@ -27,6 +27,35 @@ __device__ __forceinline__ void body(int iters, float seed, const bf16x8* lds, f
   bf16x8 r[8];
   for (int i = 0; i < 8; ++i) r[i] = a;
   for (int it = 0; it < iters; ++it) {
+    if (W == MIX || W == MIX_TR) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r[2 * i], b, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r[2 * i + 1], b, acc1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (W == MIX) {
+          r[i] = lds[(threadIdx.x & 63) + 64 * ((i + it) & 15)];
+        } else {   // two 64-bit transposing reads per operand
+          typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+          const __bf16* p = reinterpret_cast<const __bf16*>(&lds[64 * ((i + it) & 15)]) + 4 * (threadIdx.x & 63);
+          bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p));
+          bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p + 256));
+          r[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = __builtin_amdgcn_exp2f(v[i]);
+#pragma unroll
+      for (int j = 0; j < 36; ++j) v[8 + (j & 7)] = __builtin_fmaf(v[8 + (j & 7)], 1.0001f, 0.5f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x8, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, W == MIX ? 1 : 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x2, 6, 0);
+      }
+    }
     if (W == MFMA || W == MFMA_FMA || W == MFMA_EXP || W == MFMA_LDS) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -127,5 +156,9 @@ int main() {
   run<MFMA_FMA, MFMA_FMA>("A=B=MFMA+FMA");
   run<MFMA_EXP, MFMA_EXP>("A=B=MFMA+EXP");
   run<MFMA_LDS, MFMA_LDS>("A=B=MFMA<-LDS");
+  printf("MIX = 8 MFMA fed from 8 LDS reads + 36 FMA + 8 EXP per iteration (an attention kernel's mix per MFMA); _TR: transposing reads\n");
+  run<MIX, NONE>("A=MIX alone");
+  run<MIX, MIX>("A=B=MIX");
+  run<MIX_TR, MIX_TR>("A=B=MIX_TR");
   return 0;
 }
