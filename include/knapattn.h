@@ -55,7 +55,15 @@ extern "C" {
  * n_seq == 0 succeeds and enqueues nothing.
  * ------------------------------------------------------------------------ */
 
-/* out = softmax(scale * q k^T) v per (sequence, head); also writes lse. */
+/* out = softmax(scale * q k^T) v per (sequence, head); also writes lse.
+ *
+ * Concurrency.  The kernel draws its work items from counters that live in the
+ * library's device image: 256 sets, handed out in rotation, each cleared on
+ * `stream` right before the kernel that uses it.  Calls from several threads
+ * and on several streams may overlap freely as long as no more than 256
+ * forward launches are in flight on a device at the same time.  The first call
+ * on a device (it looks up device properties) must not be made under stream
+ * capture; later calls may be captured. */
 int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
                          const int32_t* cu_seqlens, int n_seq,
                          int H, int d, float scale,
