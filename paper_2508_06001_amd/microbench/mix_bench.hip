@@ -9,7 +9,7 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("HIP error %s line %d\n", hipGetErrorString(e), __LINE__); exit(1);} } while (0)
-// per iteration: 8 MFMAs, NL LDS b128 reads (operands when NL == 8), NF fmas, NE exps; PRIO: s_setprio 1 around nothing/ whole loop
+// per iteration: 8 MFMAs, NL LDS b128 reads (operands when NL == 8 or 4), NF fmas, NE exps; PRIO: s_setprio 1 around nothing/ whole loop
 template <int NF, int NE, int NL, int PRIO, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void k(float* out, long long* clk, int iters, float seed) {
   __shared__ bf16x8 lds[64 * 16];
@@ -28,8 +28,9 @@ __global__ __launch_bounds__(64 * WAVES) void k(float* out, long long* clk, int 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (PRIO == 2) __builtin_amdgcn_s_setprio(1);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(NL == 8 ? r[2 * i] : a, b, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(NL == 8 ? r[2 * i + 1] : a, b, acc1, 0, 0, 0);
+      // NL == 4: every operand read feeds two MFMAs (a 64 x 64 register block per wave)
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(NL == 8 ? r[2 * i] : NL == 4 ? r[i] : a, b, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(NL == 8 ? r[2 * i + 1] : NL == 4 ? r[i] : a, b, acc1, 0, 0, 0);
       if (PRIO == 2) __builtin_amdgcn_s_setprio(0);
     }
 #pragma unroll
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(64 * WAVES) void k(float* out, long long* clk, int 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x8, 1, 0);
-      if (NL) __builtin_amdgcn_sched_group_barrier(0x100, NL / 8, 0);
+      if (NL >= 8 || (NL == 4 && (i & 1))) __builtin_amdgcn_sched_group_barrier(0x100, NL >= 8 ? NL / 8 : 1, 0);
       if (NF + NE) __builtin_amdgcn_sched_group_barrier(0x2, (NF + NE + 7) / 8, 0);
     }
   }
@@ -78,5 +79,10 @@ int main() {
   run<36, 8, 8, 0, 12>("36 FMA + 8 EXP + 8 LDS");
   run<36, 8, 8, 0, 16>("36 FMA + 8 EXP + 8 LDS");
   run<16, 8, 8, 0, 16>("16 FMA + 8 EXP + 8 LDS");
+  run<36, 8, 4, 0, 4>("36 FMA + 8 EXP + 4 LDS (each read feeds 2)");
+  run<36, 8, 4, 0, 8>("36 FMA + 8 EXP + 4 LDS (each read feeds 2)");
+  run<28, 8, 4, 0, 4>("28 FMA + 8 EXP + 4 LDS (each read feeds 2)");
+  run<28, 8, 4, 0, 8>("28 FMA + 8 EXP + 4 LDS (each read feeds 2)");
+  run<36, 8, 0, 0, 4>("36 FMA + 8 EXP, no LDS");
   return 0;
 }
