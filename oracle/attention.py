@@ -22,6 +22,12 @@ definition, evaluated in float64 for every (sequence, head) independently:
     dQ  = scale * dS K
     dK  = scale * dS^T Q
 
+The other homogeneous mask the paper admits inside a datum (Limitations
+paragraph: bidirectional full attention or causal attention) is the same
+definition with S_ij = -inf for j > i, i and j counted from the start of the
+sequence: ``causal=True``.  A masked score has P_ij = 0 and takes no part in any
+sum; row i then depends on keys 0..i only.
+
 Matrix products use numpy's matmul (a library primitive per step).  Long
 sequences are evaluated a block of query rows at a time only to bound memory:
 every row still sees its whole row of scores, there is no online softmax.
@@ -56,7 +62,12 @@ def softmax_rows(S: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return E / l, (m + np.log(l))[:, 0]
 
 
-def attn_fwd_dense(Q, K, V, scale: float) -> Tuple[np.ndarray, np.ndarray]:
+def _mask_future_keys(S: np.ndarray, rows: np.ndarray) -> None:
+    """Causal mask, in place: score (i, j) of query row rows[i] is -inf where j > rows[i]."""
+    S[np.arange(S.shape[1])[None, :] > np.asarray(rows)[:, None]] = -np.inf
+
+
+def attn_fwd_dense(Q, K, V, scale: float, causal: bool = False) -> Tuple[np.ndarray, np.ndarray]:
     """One sequence, one head.  Q, K, V: (L, d).  Returns O (L, d) and LSE (L,)."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     L = Q.shape[0]
@@ -66,13 +77,15 @@ def attn_fwd_dense(Q, K, V, scale: float) -> Tuple[np.ndarray, np.ndarray]:
     for r0 in range(0, L, rb):
         r1 = min(L, r0 + rb)
         S = scale * (Q[r0:r1] @ K.T)
+        if causal:
+            _mask_future_keys(S, np.arange(r0, r1))
         P, lse = softmax_rows(S)
         O[r0:r1] = P @ V
         LSE[r0:r1] = lse
     return O, LSE
 
 
-def attn_bwd_dense(Q, K, V, dO, scale: float) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def attn_bwd_dense(Q, K, V, dO, scale: float, causal: bool = False) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """One sequence, one head.  Gradients of sum(dO * O) with respect to Q, K, V."""
     Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
     L = Q.shape[0]
@@ -83,6 +96,8 @@ def attn_bwd_dense(Q, K, V, dO, scale: float) -> Tuple[np.ndarray, np.ndarray, n
     for r0 in range(0, L, rb):
         r1 = min(L, r0 + rb)
         S = scale * (Q[r0:r1] @ K.T)
+        if causal:
+            _mask_future_keys(S, np.arange(r0, r1))
         P, _ = softmax_rows(S)
         dV += P.T @ dO[r0:r1]
         dP = dO[r0:r1] @ V.T
@@ -93,7 +108,8 @@ def attn_bwd_dense(Q, K, V, dO, scale: float) -> Tuple[np.ndarray, np.ndarray, n
     return dQ, dK, dV
 
 
-def varlen_attn_fwd(q, k, v, cu_seqlens: Sequence[int], scale: float) -> Tuple[np.ndarray, np.ndarray]:
+def varlen_attn_fwd(q, k, v, cu_seqlens: Sequence[int], scale: float,
+                    causal: bool = False) -> Tuple[np.ndarray, np.ndarray]:
     """Packed forward.  q, k, v: (T, H, d).  Returns out (T, H, d) and lse (H, T), float64.
 
     Each sequence is sliced out and attended on its own; nothing is ever formed
@@ -108,13 +124,13 @@ def varlen_attn_fwd(q, k, v, cu_seqlens: Sequence[int], scale: float) -> Tuple[n
         if r1 <= r0:
             continue
         for h in range(H):
-            O, LSE = attn_fwd_dense(q[r0:r1, h, :], k[r0:r1, h, :], v[r0:r1, h, :], scale)
+            O, LSE = attn_fwd_dense(q[r0:r1, h, :], k[r0:r1, h, :], v[r0:r1, h, :], scale, causal)
             out[r0:r1, h, :] = O
             lse[h, r0:r1] = LSE
     return out, lse
 
 
-def varlen_attn_bwd(q, k, v, cu_seqlens: Sequence[int], scale: float, dout):
+def varlen_attn_bwd(q, k, v, cu_seqlens: Sequence[int], scale: float, dout, causal: bool = False):
     """Packed backward.  Returns dq, dk, dv, each (T, H, d) float64."""
     T, H, d = np.shape(q)
     dq = np.zeros((T, H, d), dtype=np.float64)
@@ -127,7 +143,7 @@ def varlen_attn_bwd(q, k, v, cu_seqlens: Sequence[int], scale: float, dout):
             continue
         for h in range(H):
             dQ, dK, dV = attn_bwd_dense(q[r0:r1, h, :], k[r0:r1, h, :], v[r0:r1, h, :],
-                                        dout[r0:r1, h, :], scale)
+                                        dout[r0:r1, h, :], scale, causal)
             dq[r0:r1, h, :] = dQ
             dk[r0:r1, h, :] = dK
             dv[r0:r1, h, :] = dV
@@ -138,7 +154,7 @@ def varlen_attn_bwd(q, k, v, cu_seqlens: Sequence[int], scale: float, dout):
 # Exact evaluation of selected outputs of one long (sequence, head)
 # ---------------------------------------------------------------------------
 
-def attn_query_rows(Q, K, V, dO, rows: Sequence[int], scale: float):
+def attn_query_rows(Q, K, V, dO, rows: Sequence[int], scale: float, causal: bool = False):
     """Exact O, LSE and dQ for the chosen query rows of one (sequence, head).
 
     A query row depends only on its own q and dO rows and on all of K and V, so
@@ -150,6 +166,8 @@ def attn_query_rows(Q, K, V, dO, rows: Sequence[int], scale: float):
     Qr = _f64(np.asarray(Q)[rows])
     dOr = _f64(np.asarray(dO)[rows])
     S = scale * (Qr @ K.T)
+    if causal:
+        _mask_future_keys(S, rows)
     P, lse = softmax_rows(S)
     O = P @ V
     dP = dOr @ V.T
@@ -159,7 +177,7 @@ def attn_query_rows(Q, K, V, dO, rows: Sequence[int], scale: float):
     return O, lse, dQ
 
 
-def attn_key_cols(Q, K, V, dO, cols: Sequence[int], scale: float):
+def attn_key_cols(Q, K, V, dO, cols: Sequence[int], scale: float, causal: bool = False):
     """Exact dK and dV for the chosen key/value rows of one (sequence, head).
 
     Needs LSE_i and D_i of every query row, so one full forward pass over the
@@ -168,10 +186,12 @@ def attn_key_cols(Q, K, V, dO, cols: Sequence[int], scale: float):
     """
     cols = np.asarray(cols, dtype=np.int64)
     Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
-    O, LSE = attn_fwd_dense(Q, K, V, scale)
+    O, LSE = attn_fwd_dense(Q, K, V, scale, causal)
     D = (dO * O).sum(axis=1)
     Kc, Vc = K[cols], V[cols]
     Sc = scale * (Q @ Kc.T)                 # (L, n_cols)
+    if causal:                              # key cols[c] is in the future of query i when cols[c] > i
+        Sc[cols[None, :] > np.arange(Q.shape[0])[:, None]] = -np.inf
     Pc = np.exp(Sc - LSE[:, None])
     dPc = dO @ Vc.T
     dSc = Pc * (dPc - D[:, None])
