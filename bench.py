@@ -70,19 +70,27 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def flops_fwd(bag) -> float:
-    return 4.0 * bag.H * bag.d * bag.sum_l2
+def score_count(bag, causal: bool = False) -> float:
+    """Scores (query, key) pairs per head that the method must form: sum L^2, or under the causal
+    mask sum L (L + 1) / 2 (masked pairs are not work)."""
+    if not causal:
+        return float(bag.sum_l2)
+    return float(sum(L * (L + 1) // 2 for L in bag.seq_lens))
 
 
-def flops_bwd(bag) -> float:
-    return 10.0 * bag.H * bag.d * bag.sum_l2
+def flops_fwd(bag, causal: bool = False) -> float:
+    return 4.0 * bag.H * bag.d * score_count(bag, causal)
 
 
-def flops_dkdv_kernel(bag) -> float:
+def flops_bwd(bag, causal: bool = False) -> float:
+    return 10.0 * bag.H * bag.d * score_count(bag, causal)
+
+
+def flops_dkdv_kernel(bag, causal: bool = False) -> float:
     """Algorithmic FLOPs credited to the dK/dV kernel: the recompute of S and dP (4) plus dV and dK (4).
     The dQ kernel recomputes S and dP a second time; that repeat is not algorithmic work and is
     credited to nobody, so forward (4) + dK/dV kernel (8) + dQ kernel (2) = 14 H d sum(L^2)."""
-    return 8.0 * bag.H * bag.d * bag.sum_l2
+    return 8.0 * bag.H * bag.d * score_count(bag, causal)
 
 
 def device_inputs(bag, seed_tensors=True):
@@ -113,13 +121,13 @@ def device_inputs_fast(bag, seed=0):
     return dev
 
 
-def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
+def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents, causal: bool = False):
     """Returns dict of per-step ms: total, fwd, bwd (whole call), bwd_main (dominant kernel)."""
     import torch
     import paper_2508_06001_amd as K
     from knap_inputs import cu_seqlens_of
 
-    attn = K.VarlenAttention(cu_seqlens_of(bag.seq_lens), bag.H, bag.d, bag.scale)
+    attn = K.VarlenAttention(cu_seqlens_of(bag.seq_lens), bag.H, bag.d, bag.scale, causal=causal)
     attn._ensure_bwd_buffers()
     stream = int(torch.cuda.current_stream().cuda_stream)
     sets = dev if isinstance(dev, (list, tuple)) else [dev]   # input sets, used in rotation
@@ -167,7 +175,7 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents):
     }
 
 
-def cpu_baseline(bag, bits, budget_s: float = 20.0):
+def cpu_baseline(bag, bits, budget_s: float = 20.0, causal: bool = False):
     """The fp64 oracle, as it stands, on the host cores: forward + backward of whole
     (sequence, head) units of the same bag, added longest-first-agnostic in bag order
     for head 0, 1, ... until about `budget_s` seconds of CPU work have been spent."""
@@ -190,9 +198,9 @@ def cpu_baseline(bag, bits, budget_s: float = 20.0):
                 continue
             sl = slice(int(cu[s]), int(cu[s + 1]))
             Q, K_, V, dO = (bf16_bits_to_f32(bits[n][sl, h, :]).astype(np.float64) for n in ("q", "k", "v", "dout"))
-            A.attn_fwd_dense(Q, K_, V, bag.scale)
-            A.attn_bwd_dense(Q, K_, V, dO, bag.scale)
-            done_flops += 14.0 * bag.d * L * L
+            A.attn_fwd_dense(Q, K_, V, bag.scale, causal)
+            A.attn_bwd_dense(Q, K_, V, dO, bag.scale, causal)
+            done_flops += 14.0 * bag.d * (L * (L + 1) / 2 if causal else L * L)
             units += 1
             if time.perf_counter() - t0 > budget_s:
                 stop = True
@@ -239,12 +247,13 @@ def run_default(args):
         torch.cuda.synchronize()
         del src, dst
     ev = HipEvents()
-    r = time_bag(bag, dev, args.steps, args.warmup, ev)
+    causal = bool(args.causal)
+    r = time_bag(bag, dev, args.steps, args.warmup, ev, causal)
     ms = r["gpu_ms_per_step"]
-    total_flops = flops_fwd(bag) + flops_bwd(bag)
+    total_flops = flops_fwd(bag, causal) + flops_bwd(bag, causal)
     value = total_flops / (ms * 1e-3) / 1e12
-    bwd_main_tflops = flops_dkdv_kernel(bag) / (r["bwd_main_ms"] * 1e-3) / 1e12
-    fwd_tflops = flops_fwd(bag) / (r["fwd_ms"] * 1e-3) / 1e12
+    bwd_main_tflops = flops_dkdv_kernel(bag, causal) / (r["bwd_main_ms"] * 1e-3) / 1e12
+    fwd_tflops = flops_fwd(bag, causal) / (r["fwd_ms"] * 1e-3) / 1e12
     log(f"[bench] ms/step={ms:.3f} (wall {r['wall_ms_per_step']:.3f}) fwd={r['fwd_ms']:.3f} ms ({fwd_tflops:.1f} TF/s) "
         f"bwd={r['bwd_ms']:.3f} ms, dK/dV kernel={r['bwd_main_ms']:.3f} ms ({bwd_main_tflops:.1f} TF/s), "
         f"dQ kernel (with delta)={r['bwd_ms'] - r['bwd_main_ms']:.3f} ms")
@@ -253,10 +262,12 @@ def run_default(args):
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {bag.name}", "n_seq": len(bag.seq_lens),
+        "config": {"workload": f"configs[{args.config}] {bag.name}" + (" (causal mask)" if causal else ""),
+                   "n_seq": len(bag.seq_lens),
                    "total_tokens": bag.total_tokens, "H": bag.H, "d": bag.d, "max_len": max(bag.seq_lens),
                    "seed": bag.seed, "flops_per_step": total_flops,
-                   "flop_convention": "14*H*d*sum(L^2) (4 fwd + 10 recompute bwd)"},
+                   "flop_convention": "14*H*d*sum(L(L+1)/2) (4 fwd + 10 recompute bwd; masked pairs not counted)"
+                   if causal else "14*H*d*sum(L^2) (4 fwd + 10 recompute bwd)"},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "paper_convention_tflops": round(value * 12.0 / 14.0, 3),
         "fwd_ms": round(r["fwd_ms"], 4), "bwd_ms": round(r["bwd_ms"], 4),
@@ -267,14 +278,15 @@ def run_default(args):
         "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel", "achieved": round(bwd_main_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_main_tflops / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_ms": round(r["bwd_main_ms"], 4),
-                     "flops_per_launch": flops_dkdv_kernel(bag),
-                     "traffic": measured_traffic(f"configs[{args.config}]", "attn_bwd_dkdv_kernel")},
+                     "flops_per_launch": flops_dkdv_kernel(bag, causal),
+                     "traffic": None if causal else
+                     measured_traffic(f"configs[{args.config}]", "attn_bwd_dkdv_kernel")},
     }
     if not args.no_cpu_baseline:
         if bits is None:
             from knap_inputs import make_qkv_dout
             bits = make_qkv_dout(bag)
-        cb = cpu_baseline(bag, bits, args.cpu_budget)
+        cb = cpu_baseline(bag, bits, args.cpu_budget, causal)
         log(f"[bench] cpu oracle: {cb['value'] * 1e3:.2f} GFLOP/s on {cb['cores']} threads ({cb['sample']})")
         out["cpu_baseline"] = {**cb, "value": round(cb["value"], 6)}
     print(json.dumps(out), flush=True)
@@ -403,6 +415,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4 (default 1)")
+    ap.add_argument("--causal", action="store_true",
+                    help="time the causal entry points (not the headline workload) on the same bag")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")

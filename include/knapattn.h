@@ -93,6 +93,28 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
 
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d);
 
+/* The same two calls under the other homogeneous mask the paper admits inside a
+ * datum (Limitations paragraph: bidirectional full attention or causal
+ * attention): row i of a sequence attends to rows 0..i of that sequence only,
+ * i counted from the sequence's first row; lse is the log-sum over those keys.
+ * Arguments, layouts, workspace (same size query), concurrency and error
+ * behaviour are exactly those of knap_varlen_attn_fwd / knap_varlen_attn_bwd;
+ * `out` and `lse` given to the backward must come from the causal forward. */
+int knap_varlen_attn_causal_fwd(const void* q, const void* k, const void* v,
+                                const int32_t* cu_seqlens, int n_seq,
+                                int H, int d, float scale,
+                                void* out, float* lse,
+                                void* stream);
+int knap_varlen_attn_causal_bwd(const void* q, const void* k, const void* v,
+                                const int32_t* cu_seqlens, int n_seq,
+                                int H, int d, float scale,
+                                const void* out, const float* lse,
+                                const void* dout,
+                                void* dq, void* dk, void* dv,
+                                int64_t total_tokens,
+                                void* workspace, size_t workspace_bytes,
+                                void* stream);
+
 /* Message for a KNAP_ERR_* code (static string, never NULL). */
 const char* knap_strerror(int code);
 

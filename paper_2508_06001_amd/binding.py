@@ -43,6 +43,8 @@ _SIGNATURES = {
     "knap_varlen_attn_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp]),
     "knap_varlen_attn_bwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "knap_varlen_attn_bwd_workspace_bytes": (_sz, [_i64, _i, _i, _i]),
+    "knap_varlen_attn_causal_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp]),
+    "knap_varlen_attn_causal_bwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "knap_strerror": (C.c_char_p, [_i]),
     "knap_last_hip_error": (_i, []),
     "knap_launch_workgroups": (_i, [_i]),
@@ -125,6 +127,30 @@ def knap_varlen_attn_bwd(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale:
                                   total_tokens, _ptr(workspace), workspace_bytes, _stream_handle(stream))
     if check:
         _check(rc, "knap_varlen_attn_bwd")
+    return rc
+
+
+def knap_varlen_attn_causal_fwd(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale: float, out, lse,
+                                stream=None, check: bool = True) -> int:
+    """knap_varlen_attn_fwd with the causal mask inside every sequence."""
+    rc = lib.knap_varlen_attn_causal_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), n_seq, H, d, scale,
+                                         _ptr(out), _ptr(lse), _stream_handle(stream))
+    if check:
+        _check(rc, "knap_varlen_attn_causal_fwd")
+    return rc
+
+
+def knap_varlen_attn_causal_bwd(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale: float, out, lse, dout,
+                                dq, dk, dv, total_tokens: int, workspace, workspace_bytes: Optional[int] = None,
+                                stream=None, check: bool = True) -> int:
+    """knap_varlen_attn_bwd with the causal mask inside every sequence."""
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.knap_varlen_attn_causal_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), n_seq, H, d, scale,
+                                         _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                                         total_tokens, _ptr(workspace), workspace_bytes, _stream_handle(stream))
+    if check:
+        _check(rc, "knap_varlen_attn_causal_bwd")
     return rc
 
 

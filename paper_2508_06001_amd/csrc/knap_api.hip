@@ -63,14 +63,8 @@ int check_common(const void* q, const void* k, const void* v, const int32_t* cu,
   return KNAP_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
-                         const int32_t* cu_seqlens, int n_seq,
-                         int H, int d, float scale,
-                         void* out, float* lse, void* stream) {
+int fwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seq,
+             int H, int d, float scale, bool causal, void* out, float* lse, void* stream) {
   const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d, scale);
   if (rc != KNAP_OK) return rc;
   if (n_seq == 0) return KNAP_OK;
@@ -80,10 +74,33 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
   const int grid = di->cus * di->fwd_wg[d == 128];
   unsigned* counters = di->fwd_queue + 8u * (g_fwd_launches.fetch_add(1u) % (unsigned)knap::fwd_queue_slots());
-  const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, counters, grid,
-                                        static_cast<hipStream_t>(stream));
+  const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, causal, out, lse, counters,
+                                        grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;
+}
+
+int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seq,
+             int H, int d, float scale, bool causal,
+             const void* out, const float* lse, const void* dout, void* dq, void* dk, void* dv,
+             int64_t total_tokens, void* workspace, size_t workspace_bytes, void* stream);
+
+}  // namespace
+
+extern "C" {
+
+int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, int n_seq,
+                         int H, int d, float scale,
+                         void* out, float* lse, void* stream) {
+  return fwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, false, out, lse, stream);
+}
+
+int knap_varlen_attn_causal_fwd(const void* q, const void* k, const void* v,
+                                const int32_t* cu_seqlens, int n_seq,
+                                int H, int d, float scale,
+                                void* out, float* lse, void* stream) {
+  return fwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, true, out, lse, stream);
 }
 
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d) {
@@ -100,6 +117,29 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          void* dq, void* dk, void* dv,
                          int64_t total_tokens,
                          void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, false, out, lse, dout, dq, dk, dv, total_tokens,
+                  workspace, workspace_bytes, stream);
+}
+
+int knap_varlen_attn_causal_bwd(const void* q, const void* k, const void* v,
+                                const int32_t* cu_seqlens, int n_seq,
+                                int H, int d, float scale,
+                                const void* out, const float* lse, const void* dout,
+                                void* dq, void* dk, void* dv,
+                                int64_t total_tokens,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, true, out, lse, dout, dq, dk, dv, total_tokens,
+                  workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seq,
+             int H, int d, float scale, bool causal,
+             const void* out, const float* lse, const void* dout, void* dq, void* dk, void* dv,
+             int64_t total_tokens, void* workspace, size_t workspace_bytes, void* stream) {
   const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d, scale);
   if (rc != KNAP_OK) return rc;
   if (total_tokens < 0 || total_tokens > INT32_MAX) return KNAP_ERR_INVALID_ARG;
@@ -119,12 +159,16 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
   unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
   const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
   const int grid_dq = di->cus * di->dq_wg[d == 128];
-  const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, out, lse, dout, dq, dk, dv,
-                                        delta, counters, grid_dkdv, grid_dq,
+  const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, causal, out, lse, dout,
+                                        dq, dk, dv, delta, counters, grid_dkdv, grid_dq,
                                         static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 const char* knap_strerror(int code) {
   switch (code) {

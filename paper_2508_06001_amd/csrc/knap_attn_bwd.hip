@@ -27,6 +27,8 @@
 #include "knap_device.h"
 #include "knap_kernels.h"
 
+#include <type_traits>
+
 namespace knap {
 
 template <int D>
@@ -61,7 +63,14 @@ __global__ void bwd_queue_reset_kernel(unsigned* __restrict__ counters) {
 // of the second products; dO and Q enter those through transposing LDS reads.  The exchange is one
 // way (dV wave -> dK wave, double buffered) and the query-side tiles live in a ring of three
 // buffers, so one workgroup barrier per tile covers every hand-over.
-template <int D>
+//
+// CAUSAL (query i sees keys 0..i): a key tile starting at row kv0 only meets the queries from row kv0
+// on.  The walk over them runs BACKWARDS, from the sequence's last query tile down to the two tiles that
+// cross the diagonal (which get the mask): workgroups on different key tiles of one (sequence, head)
+// then read the same query tiles at the same time, as they do without the mask, instead of each
+// starting at its own diagonal.  Work items are pairs of key tiles of equal total cost (see
+// build_schedule).
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
@@ -78,7 +87,7 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
   __shared__ __attribute__((aligned(16))) u32x4 sP[4][2][2 * C::MB][64];  // [pair][parity][chunk of 16 queries][lane]
   static_assert(sizeof(sP) >= sizeof(int) * C::THREADS, "scan scratch must fit in the exchange buffer");
 
-  const int n_items = build_schedule<C::BN, C::THREADS>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
+  const int n_items = build_schedule<C::BN, C::THREADS, CAUSAL>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -106,14 +115,23 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
   for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
     const int w = serpentine_item(round, wg, (int)gridDim.x);
     if (w >= n_items) continue;
-    const WorkItem it = decode_item<C::BN>(w, cu, n_seq, s_order, s_start);
+    const WorkItem it = decode_item<C::BN, CAUSAL>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
-    const int kv0 = it.tile * C::BN;
     const size_t head_off = (size_t)it.head * D;
-    const __bf16* q_base = q + (size_t)it.row0 * row_stride + head_off;
-    const __bf16* do_base = dout + (size_t)it.row0 * row_stride + head_off;
-    const float* lse_base = lse + (size_t)it.head * T + it.row0;
-    const float* delta_base = delta + (size_t)it.head * T + it.row0;
+    // CAUSAL: the item is the pair of key tiles {p, kv_tiles - 1 - p}, the one with more queries first
+    const int kv_tiles = (L + C::BN - 1) / C::BN;
+    for (int sub = 0; sub < (CAUSAL ? 2 : 1); ++sub) {
+    const int kv_tile = !CAUSAL ? it.tile : sub == 0 ? it.tile : kv_tiles - 1 - it.tile;
+    if (CAUSAL && sub == 1 && kv_tile == it.tile) break;   // the middle tile of an odd count
+    const int kv0 = kv_tile * C::BN;
+    // queries this key tile meets: rows q_first .. L - 1 of the sequence; the walk below counts its
+    // tiles and rows from q_first
+    const int q_first = CAUSAL ? kv0 : 0;
+    const int Lq = L - q_first;
+    const __bf16* q_base = q + (size_t)(it.row0 + q_first) * row_stride + head_off;
+    const __bf16* do_base = dout + (size_t)(it.row0 + q_first) * row_stride + head_off;
+    const float* lse_base = lse + (size_t)it.head * T + it.row0 + q_first;
+    const float* delta_base = delta + (size_t)it.head * T + it.row0 + q_first;
 
     // this wave's 32 key rows of K (dV wave) or V (dK wave) as B operands; rows past the end read as zero
     bf16x8 kvf[C::KC];
@@ -130,7 +148,7 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
 #pragma unroll
     for (int nb = 0; nb < C::NB; ++nb) acc[nb] = zero16();
 
-    const int n_tiles = (L + C::BM - 1) / C::BM;
+    const int n_tiles = (Lq + C::BM - 1) / C::BM;
 
     // A query-side tile travels global -> registers -> LDS.  Under load a tile's loads take longer
     // than one step's arithmetic, so TWO tiles are kept in flight: tile t + 2 is requested at the
@@ -145,8 +163,9 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
 
     // nothing here may wait for a load: the data is first touched in commit_tile
     auto fetch_tile = [&](int t, Staged& st) {
-      const int q0 = t * C::BM;
-      const uint32_t bytes = (uint32_t)max(0, min(L - q0, C::BM)) * row_bytes;   // past the end: zeros
+      // step t works on query tile t, or (CAUSAL) on tile n_tiles - 1 - t; both counted from q_first
+      const int q0 = (CAUSAL ? n_tiles - 1 - t : t) * C::BM;
+      const uint32_t bytes = (uint32_t)((CAUSAL && t >= n_tiles) ? 0 : max(0, min(Lq - q0, C::BM))) * row_bytes;   // past the end: zeros
       const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, bytes);
       const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, bytes);
 #pragma unroll
@@ -156,7 +175,7 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
         st.d[p] = buffer_load16(rd, off);
       }
       const int r = tid & (C::BM - 1);          // every row is fetched by THREADS / BM threads
-      st.ok = q0 + r < L;
+      st.ok = q0 + r < Lq && !(CAUSAL && t >= n_tiles);
       const int qi = st.ok ? q0 + r : 0;
       st.lse = lse_base[qi];
       st.delta = delta_base[qi];
@@ -173,7 +192,9 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     };
 
     // dV wave, tile t in buffer b: S, P, hand P over, dV += P^T dO
-    auto dv_step = [&](int t, int b) {
+    // (DIAG: the tile crosses the causal diagonal; a query before this lane's key gets P = 0)
+    auto dv_step = [&](auto diag_tag, int t, int b) {
+      constexpr bool DIAG = decltype(diag_tag)::value;
       const __bf16* tQ = sQ[b];
       const __bf16* tdO = sdO[b];
       f32x16 s[C::MB];
@@ -188,6 +209,8 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
       // P = exp2(c S - LSE2); register r of block mb is query 32 mb + 8 (r / 4) + 4 hh + r % 4; packed so
       // that element e of chunk cq is query 16 cq + 8 (e / 4) + 4 hh + e % 4
       bf16x8 pa[2 * C::MB];
+      // counted from the tile's first query, this lane's key is the first one that query `first_seen` sees
+      const int first_seen = 32 * pair + l32 - (n_tiles - 1 - t) * C::BM - 4 * hh;
 #pragma unroll
       for (int mb = 0; mb < C::MB; ++mb) {
         float p[16];
@@ -195,7 +218,10 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
         for (int g = 0; g < 4; ++g) {
           const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[b][32 * mb + 8 * g + 4 * hh]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) p[4 * g + e] = fast_exp2(__builtin_fmaf(s[mb][4 * g + e], c, -l4[e]));
+          for (int e = 0; e < 4; ++e) {
+            const float pe = fast_exp2(__builtin_fmaf(s[mb][4 * g + e], c, -l4[e]));
+            p[4 * g + e] = (DIAG && 32 * mb + 8 * g + e < first_seen) ? 0.f : pe;
+          }
         }
         pa[2 * mb] = pack8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
         pa[2 * mb + 1] = pack8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
@@ -261,10 +287,10 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
 
     // step t: the dV wave works on tile t, the dK wave on tile t - 1, tile t + 1 sits in registers
     // (`staged`) and tile t + 2 is requested (`incoming`)
-    auto step = [&](int t, Staged& incoming, const Staged& staged) {
+    auto step = [&](auto diag_tag, int t, Staged& incoming, const Staged& staged) {
       fetch_tile(t + 2, incoming);         // past the end: an empty descriptor, every lane reads zero
       if (role == 0) {
-        if (t < n_tiles) dv_step(t, t % C::NBUF);
+        if (t < n_tiles) dv_step(diag_tag, t, t % C::NBUF);
       } else {
         if (t >= 1 && t <= n_tiles) dk_step(t - 1, (t - 1) % C::NBUF);
       }
@@ -274,11 +300,26 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     // steps 0 .. n_tiles.  The loop body is two unconditional steps (a step under a condition inside
     // the loop would make the load counts inexact); an odd step left over is taken after it.
     int t = 0;
-    for (; t + 1 <= n_tiles; t += 2) {
-      step(t, stA, stB);
-      step(t + 1, stB, stA);
+    if constexpr (!CAUSAL) {
+      for (; t + 1 <= n_tiles; t += 2) {
+        step(std::false_type{}, t, stA, stB);
+        step(std::false_type{}, t + 1, stB, stA);
+      }
+      if (t <= n_tiles) step(std::false_type{}, t, stA, stB);
+    } else {
+      // the two tiles that cross the diagonal come last (steps n_tiles - 2 and n_tiles - 1); the unmasked
+      // loop runs up to the even step at or below n_tiles - 2, the two to four steps after it take the mask
+      // (which hides nothing in a tile above the diagonal)
+      const int n_plain = max(0, n_tiles - 2) & ~1;
+      for (; t < n_plain; t += 2) {
+        step(std::false_type{}, t, stA, stB);
+        step(std::false_type{}, t + 1, stB, stA);
+      }
+      step(std::true_type{}, t, stA, stB);
+      step(std::true_type{}, t + 1, stB, stA);        // n_tiles >= 1: step n_plain + 1 exists
+      if (t + 2 <= n_tiles) step(std::true_type{}, t + 2, stA, stB);
+      if (t + 3 <= n_tiles) step(std::true_type{}, t + 3, stB, stA);
     }
-    if (t <= n_tiles) step(t, stA, stB);
 
     // this wave's rows of dV, or of dK (scaled): register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
     __bf16* dst = role == 0 ? dv : dk;
@@ -291,6 +332,7 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
         if (kv < L)
           dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[nb][r] * out_scale);
       }
+    }   // sub
   }
 }
 
@@ -303,7 +345,7 @@ struct DqCfg {
   static constexpr int TILE_ELEMS = BN * Tile<D>::LD;
 };
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ out, const __bf16* __restrict__ dout, const float* __restrict__ lse,
@@ -321,11 +363,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   __shared__ __attribute__((aligned(1024))) __bf16 sV1[C::TILE_ELEMS];
   static_assert(sizeof(__bf16) * C::TILE_ELEMS >= sizeof(int) * kThreads, "scan scratch must fit in a tile");
 
-  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
+  const int n_items = build_schedule<C::BM, kThreads, CAUSAL>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int wave_u = CAUSAL ? __builtin_amdgcn_readfirstlane(wave) : 0;   // the same number, known to be wave-uniform
   const int l32 = lane & 31;
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
@@ -348,12 +391,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
   for (;;) {
     const int w = queue.item(__builtin_amdgcn_readfirstlane(s_ticket));
     if (w >= n_items) break;
-    const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
+    const WorkItem it = decode_item<C::BM, CAUSAL>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
-    const int q0 = it.tile * C::BM;
+    const size_t head_off = (size_t)it.head * D;
+    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
+    // CAUSAL: the item is the pair of query tiles {q_tiles - 1 - p, p}, the long one first
+    const int q_tiles = (L + C::BM - 1) / C::BM;
+    int sub = 0;
+  second_tile_of_pair:;     // CAUSAL only: jumped back to once, from the end of the first tile
+    const int q_tile = !CAUSAL ? it.tile : sub == 0 ? q_tiles - 1 - it.tile : it.tile;
+    const int q0 = q_tile * C::BM;
     const int q_row = q0 + wave * 32 + l32;
     const bool q_valid = q_row < L;
-    const size_t head_off = (size_t)it.head * D;
+    // keys this query tile sees at all
+    const int kv_end = CAUSAL ? min(L, q0 + C::BM) : L;
 
     // this lane's q and dO rows as B operands (rows past the end read as zero), and
     // delta = sum_c dO_c O_c of its query: the lane holds half of the row's elements (8 of every 16),
@@ -391,12 +442,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
 
     const __bf16* k_base = k + (size_t)it.row0 * row_stride + head_off;
     const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
-    const int n_tiles = (L + C::BN - 1) / C::BN;
+    const int n_tiles = (kv_end + C::BN - 1) / C::BN;
 
     // asynchronous; rows past the end arrive as zeros and add nothing to dQ
     auto load_tile = [&](int t, __bf16* dK, __bf16* dV) {
       const int kv0 = t * C::BN;
-      const uint32_t bytes = (uint32_t)max(0, min(L - kv0, C::BN)) * row_bytes;
+      const uint32_t bytes = (uint32_t)max(0, min(kv_end - kv0, C::BN)) * row_bytes;
       tile_load_async<D>(dK, make_rsrc(k_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
       tile_load_async<D>(dV, make_rsrc(v_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
     };
@@ -404,8 +455,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     // One tile: 64 keys as two halves of 32, one after the other (the register file is full with
     // the q and dO fragments and the dQ accumulator; the second wave of the SIMD fills the gaps).
     // Within a half the LDS reads are streamed a few MFMAs ahead of their use.
-    auto process_tile = [&](int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
+    // DIAG: the tile crosses the causal diagonal; keys after this lane's query get dS = 0, and a wave
+    // whose 32 queries all precede the tile's first key has nothing to do in it.
+    auto process_tile = [&](auto diag_tag, int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
+      constexpr bool DIAG = decltype(diag_tag)::value;
       load_tile(t + 1, nK, nV);
+      if (!(DIAG && t * C::BN > q0 + 32 * wave_u + 31)) {
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         f32x16 s = zero16(), dp = zero16();
@@ -423,8 +478,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2); element e of chunk ck is key
         // 32 half + 16 ck + 8 (e / 4) + 4 hh + e % 4
         float ds[16];
+        const int last_seen = q_row - t * C::BN - 32 * half - 4 * hh;   // counted from this half's first key
 #pragma unroll
-        for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse2)) * (dp[r] - dl);
+        for (int r = 0; r < 16; ++r) {
+          const float x = fast_exp2(__builtin_fmaf(s[r], c, -lse2)) * (dp[r] - dl);
+          ds[r] = (DIAG && 8 * (r >> 2) + (r & 3) > last_seen) ? 0.f : x;
+        }
         const bf16x8 d0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
         const bf16x8 d1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
         KNAP_SCHED_FENCE();
@@ -436,6 +495,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         KNAP_SGB(KNAP_SG_MFMA, 2 * C::DB);
         KNAP_SCHED_FENCE();
       }
+      }
       wait_async_loads();
       __syncthreads();     // next tile visible; this tile no longer read
     };
@@ -443,12 +503,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     __syncthreads();       // the previous item (or the schedule build) is done with both buffers
     load_tile(0, sK0, sV0);
     wait_async_loads();
-    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
-    if (tid == 0) next_ticket = atomicAdd(queue.ctr, 1u);
+    if (tid == 0 && sub == 0) next_ticket = atomicAdd(queue.ctr, 1u);
     __syncthreads();
-    for (int t = 0; t < n_tiles; t += 2) {
-      process_tile(t, sK0, sV0, sK1, sV1);
-      if (t + 1 < n_tiles) process_tile(t + 1, sK1, sV1, sK0, sV0);
+    if constexpr (!CAUSAL) {
+      for (int t = 0; t < n_tiles; t += 2) {
+        process_tile(std::false_type{}, t, sK0, sV0, sK1, sV1);
+        if (t + 1 < n_tiles) process_tile(std::false_type{}, t + 1, sK1, sV1, sK0, sV0);
+      }
+    } else {
+      // tiles 0 .. 2 q_tile - 1 lie below the diagonal (an even count: the pair loop ends on buffer 0);
+      // tiles 2 q_tile and, if the sequence reaches it, 2 q_tile + 1 cross it
+      const int n_below = 2 * q_tile;
+      for (int t = 0; t < n_below; t += 2) {
+        process_tile(std::false_type{}, t, sK0, sV0, sK1, sV1);
+        process_tile(std::false_type{}, t + 1, sK1, sV1, sK0, sV0);
+      }
+      process_tile(std::true_type{}, n_below, sK0, sV0, sK1, sV1);
+      if (n_below + 1 < n_tiles) process_tile(std::true_type{}, n_below + 1, sK1, sV1, sK0, sV0);
     }
 
     if (q_valid) {
@@ -462,12 +533,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
           *reinterpret_cast<bf16x4*>(o_ptr + 32 * db + 8 * g + 4 * hh) = pk;
         }
     }
+    if constexpr (CAUSAL) {
+      if (sub == 0 && it.tile != q_tiles - 1 - it.tile) {   // not the middle tile of an odd count
+        sub = 1;
+        goto second_tile_of_pair;
+      }
+    }
     if (tid == 0) s_ticket = (int)next_ticket;   // every wave took its copy of the old ticket many barriers ago
     __syncthreads();
   }
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H,
                                float scale, const void* out, const float* lse, const void* dout,
                                void* dq, void* dk, void* dv, float* delta, unsigned* counters,
@@ -478,13 +555,13 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
   // the dQ kernel also produces delta, which the dK/dV kernel needs: it goes first
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, dim3(grid_dq), dim3(kThreads), dyn, stream,
+  hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL>), dim3(grid_dq), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)out,
                      (const __bf16*)dout, lse, delta, cu, n_seq, H, scale, (__bf16*)dq, counters);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<D>, dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
+  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
                      (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
   e = hipGetLastError();
@@ -494,15 +571,15 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
 }
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
-                      float scale, const void* out, const float* lse, const void* dout,
+                      float scale, bool causal, const void* out, const float* lse, const void* dout,
                       void* dq, void* dk, void* dv, float* delta, unsigned* counters,
                       int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop) {
-  if (d == 64)
-    return launch_bwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters,
-                            grid_dkdv, grid_dq, stream, ev_start, ev_stop);
-  return launch_bwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters,
-                           grid_dkdv, grid_dq, stream, ev_start, ev_stop);
+#define KNAP_BWD_ARGS q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters, \
+                      grid_dkdv, grid_dq, stream, ev_start, ev_stop
+  if (causal) return d == 64 ? launch_bwd_t<64, true>(KNAP_BWD_ARGS) : launch_bwd_t<128, true>(KNAP_BWD_ARGS);
+  return d == 64 ? launch_bwd_t<64, false>(KNAP_BWD_ARGS) : launch_bwd_t<128, false>(KNAP_BWD_ARGS);
+#undef KNAP_BWD_ARGS
 }
 
 static int occupancy_of(const void* fn, int threads = kThreads) {
@@ -515,12 +592,12 @@ static int occupancy_of(const void* fn, int threads = kThreads) {
 }
 
 int bwd_dkdv_workgroups_per_cu(int d) {
-  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64> : (const void*)attn_bwd_dkdv_kernel<128>,
+  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64, false> : (const void*)attn_bwd_dkdv_kernel<128, false>,
                       BwdCfg<128>::THREADS);
 }
 
 int bwd_dq_workgroups_per_cu(int d) {
-  return occupancy_of(d == 64 ? (const void*)attn_bwd_dq_kernel<64> : (const void*)attn_bwd_dq_kernel<128>);
+  return occupancy_of(d == 64 ? (const void*)attn_bwd_dq_kernel<64, false> : (const void*)attn_bwd_dq_kernel<128, false>);
 }
 
 }  // namespace knap

@@ -1,6 +1,8 @@
 // Forward kernel: out = softmax(scale q k^T) v per (sequence, head) of a packed
 // bag, with the row log-sum-exp (Sec. 3.4 / the attention listing of Sec. 3.5:
 // full bidirectional attention inside each sequence, none across sequences).
+// CAUSAL is the other mask the paper admits inside a datum (Limitations
+// paragraph): query i sees keys 0..i of its own sequence.
 //
 // One persistent workgroup (4 waves) takes work items (sequence, head, 128-row
 // query tile) from the longest-first schedule.  Wave w owns 32 query rows and
@@ -42,7 +44,7 @@ struct FwdCfg {
 constexpr float kRescaleThreshold = 8.0f;   // base-2 units
 constexpr int kFwdQueueSlots = 256;
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const int32_t* __restrict__ cu, int n_seq, int H, float scale,
@@ -61,11 +63,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   static_assert(sizeof(__bf16) * C::TILE_ELEMS >= sizeof(int) * kThreads, "scan scratch must fit in a tile");
 
   // the scan scratch of the schedule lives in the first K buffer, which is not in use yet
-  const int n_items = build_schedule<C::BM>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
+  const int n_items = build_schedule<C::BM, kThreads, CAUSAL>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sK0[0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int wave_u = CAUSAL ? __builtin_amdgcn_readfirstlane(wave) : 0;   // the same number, known to be wave-uniform
   const int l32 = lane & 31;
   const int hh = lane >> 5;
   const float c = scale * kLog2e;
@@ -88,12 +91,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
   for (;;) {
     const int w = queue.item(__builtin_amdgcn_readfirstlane(s_ticket));
     if (w >= n_items) break;
-    const WorkItem it = decode_item<C::BM>(w, cu, n_seq, s_order, s_start);
+    const WorkItem it = decode_item<C::BM, CAUSAL>(w, cu, n_seq, s_order, s_start);
     const int L = it.len;
-    const int q0 = it.tile * C::BM;
+    const size_t head_off = (size_t)it.head * D;
+    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
+    // CAUSAL: the item is the pair of query tiles {q_tiles - 1 - p, p}, the long one first
+    const int q_tiles = (L + C::BM - 1) / C::BM;
+    int sub = 0;
+  second_tile_of_pair:;     // CAUSAL only: jumped back to once, from the end of the first tile
+    const int q_tile = !CAUSAL ? it.tile : sub == 0 ? q_tiles - 1 - it.tile : it.tile;
+    const int q0 = q_tile * C::BM;
     const int q_row = q0 + wave * 32 + l32;      // row inside the sequence
     const bool q_valid = q_row < L;
-    const size_t head_off = (size_t)it.head * D;
+    // keys this query tile sees at all
+    const int kv_end = CAUSAL ? min(L, q0 + C::BM) : L;
 
     // this lane's query row as the B operand of S^T = K Q^T (rows past the end read as zero)
     bf16x8 qf[C::KC];
@@ -113,19 +124,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
 
     const __bf16* k_base = k + (size_t)it.row0 * row_stride + head_off;
     const __bf16* v_base = v + (size_t)it.row0 * row_stride + head_off;
-    const int n_tiles = (L + C::BN - 1) / C::BN;
+    const int n_tiles = (kv_end + C::BN - 1) / C::BN;
 
     auto load_tile = [&](int t, __bf16* dK, __bf16* dV) {   // asynchronous; a tile past the end arrives as zeros
       const int kv0 = t * C::BN;
-      const uint32_t bytes = (uint32_t)max(0, min(L - kv0, C::BN)) * row_bytes;
+      const uint32_t bytes = (uint32_t)max(0, min(kv_end - kv0, C::BN)) * row_bytes;
       tile_load_async<D>(dK, make_rsrc(k_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
       tile_load_async<D>(dV, make_rsrc(v_base + (size_t)kv0 * row_stride, bytes), row_bytes, C::BN, wave, lane);
     };
 
-    // One tile: 64 keys as two halves of 32.  MASKED is the ragged last tile.
-    auto process_tile = [&](int t, auto masked_tag, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
-      constexpr bool MASKED = decltype(masked_tag)::value;
+    // One tile: 64 keys as two halves of 32.  MODE 1 is the ragged last tile, MODE 2 a tile that
+    // crosses the causal diagonal (for rows of the sequence that mask covers the ragged end too).
+    // A wave whose 32 queries all precede the tile's first key has nothing to do in it.
+    auto process_tile = [&](int t, auto mode_tag, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
+      constexpr int MODE = decltype(mode_tag)::value;
       load_tile(t + 1, nK, nV);
+      if (!(MODE == 2 && t * C::BN > q0 + 32 * wave_u + 31)) {
 
       bf16x8 ak0[C::KC], ak1[C::KC];
 #pragma unroll
@@ -133,13 +147,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
       KNAP_SCHED_FENCE();
 
       f32x16 s0, s1;
-      if constexpr (MASKED) {   // keys past the end of the sequence start (and stay) at -inf
+      if constexpr (MODE != 0) {   // keys past the end of the sequence, or after the query, start (and stay) at -inf
         const int kv0 = t * C::BN;
+        const int kv_lim = MODE == 2 ? q_row + 1 : L;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int kv = kv0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          s0[r] = kv < L ? 0.f : -INFINITY;
-          s1[r] = kv + 32 < L ? 0.f : -INFINITY;
+          s0[r] = kv < kv_lim ? 0.f : -INFINITY;
+          s1[r] = kv + 32 < kv_lim ? 0.f : -INFINITY;
         }
       } else {
         s0 = zero16();
@@ -224,6 +239,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
 #pragma unroll
       for (int i = 0; i < C::DB; ++i) { KNAP_SGB(KNAP_SG_DS_READ, 2); KNAP_SGB(KNAP_SG_MFMA, 1); }
       KNAP_SCHED_FENCE();
+      }
       wait_async_loads();
       __syncthreads();     // next tile visible; this tile no longer read
     };
@@ -231,19 +247,33 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
     __syncthreads();       // the previous item (or the schedule build) is done with both buffers
     load_tile(0, sK0, sV0);
     wait_async_loads();
-    unsigned next_ticket;      // thread 0 only; no initial value, which would be merged in (and waited for) at once
-    if (tid == 0) next_ticket = atomicAdd(queue.ctr, 1u);
+    if (tid == 0 && sub == 0) next_ticket = atomicAdd(queue.ctr, 1u);
     __syncthreads();
 
-    const bool ragged = (L % C::BN) != 0;
-    const int n_full = ragged ? n_tiles - 1 : n_tiles;
-    for (int t = 0; t < n_full; t += 2) {
-      process_tile(t, std::false_type{}, sK0, sV0, sK1, sV1);
-      if (t + 1 < n_full) process_tile(t + 1, std::false_type{}, sK1, sV1, sK0, sV0);
-    }
-    if (ragged) {
-      if ((n_tiles - 1) & 1) process_tile(n_tiles - 1, std::true_type{}, sK1, sV1, sK0, sV0);
-      else process_tile(n_tiles - 1, std::true_type{}, sK0, sV0, sK1, sV1);
+    constexpr std::integral_constant<int, 0> plain{};
+    constexpr std::integral_constant<int, 1> ragged_end{};
+    constexpr std::integral_constant<int, 2> diagonal{};
+    if constexpr (!CAUSAL) {
+      const bool ragged = (L % C::BN) != 0;
+      const int n_full = ragged ? n_tiles - 1 : n_tiles;
+      for (int t = 0; t < n_full; t += 2) {
+        process_tile(t, plain, sK0, sV0, sK1, sV1);
+        if (t + 1 < n_full) process_tile(t + 1, plain, sK1, sV1, sK0, sV0);
+      }
+      if (ragged) {
+        if ((n_tiles - 1) & 1) process_tile(n_tiles - 1, ragged_end, sK1, sV1, sK0, sV0);
+        else process_tile(n_tiles - 1, ragged_end, sK0, sV0, sK1, sV1);
+      }
+    } else {
+      // tiles 0 .. 2 q_tile - 1 lie below the diagonal (an even count: the pair loop ends on buffer 0);
+      // tiles 2 q_tile and, if the sequence reaches it, 2 q_tile + 1 cross it
+      const int n_below = 2 * q_tile;
+      for (int t = 0; t < n_below; t += 2) {
+        process_tile(t, plain, sK0, sV0, sK1, sV1);
+        process_tile(t + 1, plain, sK1, sV1, sK0, sV0);
+      }
+      process_tile(n_below, diagonal, sK0, sV0, sK1, sV1);
+      if (n_below + 1 < n_tiles) process_tile(n_below + 1, diagonal, sK1, sV1, sK0, sV0);
     }
 
     // epilogue: normalise, store out (bf16) and lse (natural log)
@@ -261,10 +291,27 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(
         }
       if (hh == 0) lse[(size_t)it.head * T + it.row0 + q_row] = m_ref * scale + __logf(l_tot);
     }
+    if constexpr (CAUSAL) {
+      if (sub == 0 && it.tile != q_tiles - 1 - it.tile) {   // not the middle tile of an odd count
+        sub = 1;
+        goto second_tile_of_pair;
+      }
+    }
     if (tid == 0) s_ticket = (int)next_ticket;   // every wave took its copy of the old ticket many barriers ago
     __syncthreads();
   }
 }
+
+// instantiated in this order (the bidirectional kernels first)
+#define KNAP_FWD_INSTANCE(D, CAUSAL)                                                                    \
+  template __global__ void attn_fwd_kernel<D, CAUSAL>(const __bf16*, const __bf16*, const __bf16*,      \
+                                                      const int32_t*, int, int, float, __bf16*, float*, \
+                                                      unsigned*);
+KNAP_FWD_INSTANCE(64, false)
+KNAP_FWD_INSTANCE(128, false)
+KNAP_FWD_INSTANCE(64, true)
+KNAP_FWD_INSTANCE(128, true)
+#undef KNAP_FWD_INSTANCE
 
 // The forward entry point has no workspace argument, so the counters of its work queue live
 // in the library's device image: kFwdQueueSlots sets of 8 (one per XCD), handed out in rotation
@@ -288,7 +335,7 @@ unsigned* fwd_queue_base() {
   return p;
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
                                int H, float scale, void* out, float* lse, unsigned* counters, int grid,
                                hipStream_t stream) {
@@ -296,24 +343,28 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, cons
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t dyn = (size_t)(2 * n_seq + 1) * sizeof(int);
-  hipLaunchKernelGGL(attn_fwd_kernel<D>, dim3(grid), dim3(kThreads), dyn, stream,
+  hipLaunchKernelGGL((attn_fwd_kernel<D, CAUSAL>), dim3(grid), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, cu, n_seq, H, scale,
                      (__bf16*)out, lse, counters);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq,
-                      int H, int d, float scale, void* out, float* lse, unsigned* counters, int grid,
+                      int H, int d, float scale, bool causal, void* out, float* lse, unsigned* counters, int grid,
                       hipStream_t stream) {
-  if (d == 64) return launch_fwd_t<64>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
-  return launch_fwd_t<128>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
+  if (!causal) {
+    if (d == 64) return launch_fwd_t<64, false>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
+    return launch_fwd_t<128, false>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
+  }
+  if (d == 64) return launch_fwd_t<64, true>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
+  return launch_fwd_t<128, true>(q, k, v, cu, n_seq, H, scale, out, lse, counters, grid, stream);
 }
 
 int fwd_workgroups_per_cu(int d) {
   int n = 0;
   hipError_t e = (d == 64)
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_fwd_kernel<64>, kThreads, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_fwd_kernel<128>, kThreads, 0);
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_fwd_kernel<64, false>, kThreads, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_fwd_kernel<128, false>, kThreads, 0);
   if (e != hipSuccess || n < 1) { (void)hipGetLastError(); n = 1; }
   return n;
 }

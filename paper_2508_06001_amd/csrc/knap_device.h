@@ -243,6 +243,12 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
 // share one (sequence, head)'s K and V.  Every workgroup rebuilds the same
 // schedule in LDS from cu_seqlens; the host never reads cu_seqlens.
 //
+// PAIRED (causal attention): the cost of a tile grows linearly with its index
+// (query tiles) or falls linearly with it (key tiles), so tile p and tile
+// tiles - 1 - p together cost the same for every p.  An item is then such a pair
+// (the middle tile of an odd count stands alone), WorkItem::tile is p, and the
+// items of one sequence are of equal cost again.
+//
 //   s_order[r]  original index of the r-th longest sequence
 //   s_start[r]  first item of that sequence; s_start[n_seq] = number of items
 // s_start doubles as the key array of the rank sort before it is filled.
@@ -254,7 +260,10 @@ struct WorkItem {
   int tile;
 };
 
-template <int TILE, int NT = kThreads>
+template <bool PAIRED>
+__device__ __forceinline__ int items_per_head(int tiles) { return PAIRED ? (tiles + 1) >> 1 : tiles; }
+
+template <int TILE, int NT = kThreads, bool PAIRED = false>
 __device__ __forceinline__ int build_schedule(const int32_t* __restrict__ cu, int n_seq, int H,
                                               int* s_order, int* s_start, int* s_part /* NT ints */) {
   constexpr int kThreads = NT;   // threads of the calling workgroup
@@ -278,7 +287,7 @@ __device__ __forceinline__ int build_schedule(const int32_t* __restrict__ cu, in
   int local = 0;
   for (int r = lo; r < hi; ++r) {
     const int s = s_order[r];
-    local += ((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
+    local += items_per_head<PAIRED>((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
   }
   s_part[tid] = local;
   __syncthreads();
@@ -292,14 +301,14 @@ __device__ __forceinline__ int build_schedule(const int32_t* __restrict__ cu, in
   for (int r = lo; r < hi; ++r) {
     const int s = s_order[r];
     s_start[r] = run;
-    run += ((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
+    run += items_per_head<PAIRED>((cu[s + 1] - cu[s] + TILE - 1) / TILE) * H;
   }
   if (tid == kThreads - 1) s_start[n_seq] = s_part[kThreads - 1];
   __syncthreads();
   return s_start[n_seq];
 }
 
-template <int TILE>
+template <int TILE, bool PAIRED = false>
 __device__ __forceinline__ WorkItem decode_item(int w, const int32_t* __restrict__ cu, int n_seq,
                                                 const int* s_order, const int* s_start) {
   // largest r with s_start[r] <= w (sequences without items share their successor's start)
@@ -315,10 +324,10 @@ __device__ __forceinline__ WorkItem decode_item(int w, const int32_t* __restrict
   WorkItem it;
   it.row0 = __builtin_amdgcn_readfirstlane(cu[s]);
   it.len = __builtin_amdgcn_readfirstlane(cu[s + 1]) - it.row0;
-  const int tiles = (it.len + TILE - 1) / TILE;
+  const int per_head = items_per_head<PAIRED>((it.len + TILE - 1) / TILE);
   const int rem = w - first;
-  it.head = rem / tiles;
-  it.tile = rem - it.head * tiles;
+  it.head = rem / per_head;
+  it.tile = rem - it.head * per_head;
   return it;
 }
 

@@ -25,9 +25,12 @@ def bf16_device_to_bits(t: torch.Tensor) -> np.ndarray:
 
 
 class VarlenAttention:
-    """Buffers + calls for one packed bag: T tokens, H heads, head dim d."""
+    """Buffers + calls for one packed bag: T tokens, H heads, head dim d; `causal` selects the
+    causal pair of entry points."""
 
-    def __init__(self, cu_seqlens: Sequence[int], H: int, d: int, scale: float, device="cuda"):
+    def __init__(self, cu_seqlens: Sequence[int], H: int, d: int, scale: float, device="cuda",
+                 causal: bool = False):
+        self.causal = bool(causal)
         cu = np.asarray(cu_seqlens, dtype=np.int32)
         self.n_seq = int(cu.shape[0] - 1)
         self.T = int(cu[-1]) if cu.shape[0] else 0
@@ -41,8 +44,8 @@ class VarlenAttention:
         self.workspace = None
 
     def forward(self, q, k, v, stream=None):
-        B.knap_varlen_attn_fwd(q, k, v, self.cu, self.n_seq, self.H, self.d, self.scale,
-                               self.out, self.lse, stream)
+        fwd = B.knap_varlen_attn_causal_fwd if self.causal else B.knap_varlen_attn_fwd
+        fwd(q, k, v, self.cu, self.n_seq, self.H, self.d, self.scale, self.out, self.lse, stream)
         return self.out, self.lse
 
     def _ensure_bwd_buffers(self):
@@ -56,7 +59,7 @@ class VarlenAttention:
 
     def backward(self, q, k, v, dout, stream=None):
         self._ensure_bwd_buffers()
-        B.knap_varlen_attn_bwd(q, k, v, self.cu, self.n_seq, self.H, self.d, self.scale,
-                               self.out, self.lse, dout, self.dq, self.dk, self.dv,
-                               self.T, self.workspace, None, stream)
+        bwd = B.knap_varlen_attn_causal_bwd if self.causal else B.knap_varlen_attn_bwd
+        bwd(q, k, v, self.cu, self.n_seq, self.H, self.d, self.scale, self.out, self.lse, dout,
+            self.dq, self.dk, self.dv, self.T, self.workspace, None, stream)
         return self.dq, self.dk, self.dv

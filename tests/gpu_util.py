@@ -22,7 +22,7 @@ def to_f64(bits: np.ndarray) -> np.ndarray:
 class GpuRun:
     """q, k, v, dout on the device, one forward and one backward through the C ABI."""
 
-    def __init__(self, bag: BagSpec, tensors=None, backward: bool = True):
+    def __init__(self, bag: BagSpec, tensors=None, backward: bool = True, causal: bool = False):
         import torch
         import paper_2508_06001_amd as K
         from paper_2508_06001_amd.runtime import bf16_bits_to_device, bf16_device_to_bits
@@ -31,10 +31,10 @@ class GpuRun:
         self.bits = tensors if tensors is not None else make_qkv_dout(bag)
         self.cu = cu_seqlens_of(bag.seq_lens)
         say(f"[gpu] bag={bag.name} seed={bag.seed} n_seq={len(bag.seq_lens)} T={bag.total_tokens} "
-            f"H={bag.H} d={bag.d} maxL={max(bag.seq_lens) if bag.seq_lens else 0}")
+            f"H={bag.H} d={bag.d} maxL={max(bag.seq_lens) if bag.seq_lens else 0} causal={causal}")
         dev = {n: bf16_bits_to_device(self.bits[n]) for n in ("q", "k", "v", "dout")}
         self.dev = dev
-        self.attn = K.VarlenAttention(self.cu, bag.H, bag.d, bag.scale)
+        self.attn = K.VarlenAttention(self.cu, bag.H, bag.d, bag.scale, causal=causal)
         # canaries: outputs start as NaN so an unwritten element cannot pass
         self.attn.out.fill_(float("nan"))
         self.attn.lse.fill_(float("nan"))

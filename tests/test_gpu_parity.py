@@ -19,11 +19,11 @@ LSE_TOL = 3e-3      # diagnostic: the row sum is taken over bf16-rounded probabi
 BWD_TOL = 3e-2
 
 
-def _full_compare(bag: BagSpec, heads=None, strict_fwd=True):
+def _full_compare(bag: BagSpec, heads=None, strict_fwd=True, causal=False):
     """strict_fwd: the benchmark bar max |err| <= 1e-2.  The edge-case bags hold sequences of one or
     two tokens whose outputs are as large as single v entries (|out| up to ~4); there half a bf16 ulp
     of the stored output (2^-8 |ref|) alone can pass 1e-2, so the bar is max(1e-2, 2^-8 |ref|)."""
-    run = GpuRun(bag)
+    run = GpuRun(bag, causal=causal)
     heads = list(range(bag.H)) if heads is None else heads
     cu = [int(c) for c in run.cu]
     worst_fwd = worst_lse = 0.0
@@ -35,8 +35,8 @@ def _full_compare(bag: BagSpec, heads=None, strict_fwd=True):
             continue
         for h in heads:
             Q, K_, V, dO = (run.host(n, sl, h) for n in ("q", "k", "v", "dout"))
-            O, LSE = A.attn_fwd_dense(Q, K_, V, bag.scale)
-            dQ, dK, dV = A.attn_bwd_dense(Q, K_, V, dO, bag.scale)
+            O, LSE = A.attn_fwd_dense(Q, K_, V, bag.scale, causal)
+            dQ, dK, dV = A.attn_bwd_dense(Q, K_, V, dO, bag.scale, causal)
             err = np.abs(run.host("out", sl, h) - O)
             if not strict_fwd:
                 err = np.where(err <= 2.0 ** -8 * np.abs(O), 0.0, err)
@@ -48,7 +48,7 @@ def _full_compare(bag: BagSpec, heads=None, strict_fwd=True):
                 num[name] += float(((got - ref) ** 2).sum())
                 den[name] += float((ref ** 2).sum())
     errs = {n: (num[n] / den[n]) ** 0.5 if den[n] > 0 else 0.0 for n in num}
-    say(f"[parity] {bag.name}: fwd max|err|={worst_fwd:.3e} lse={worst_lse:.3e} "
+    say(f"[parity] {bag.name}{' causal' if causal else ''}: fwd max|err|={worst_fwd:.3e} lse={worst_lse:.3e} "
         f"dq={errs['dq']:.3e} dk={errs['dk']:.3e} dv={errs['dv']:.3e}")
     assert worst_fwd <= FWD_TOL
     assert worst_lse <= LSE_TOL
@@ -214,7 +214,7 @@ def test_hip_graph_replays_match_eager():
 # at any size and are checked on the GPU outputs alone.
 # ---------------------------------------------------------------------------
 
-def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0):
+def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0, causal=False):
     bag = run.bag
     cu = [int(c) for c in run.cu]
     sl = slice(cu[s], cu[s + 1])
@@ -222,7 +222,7 @@ def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0):
     rng = np.random.default_rng(seed + 17 * s + h)
     Q, K_, V, dO = (run.host(n, sl, h) for n in ("q", "k", "v", "dout"))
     rows = np.unique(np.concatenate([[0, L - 1, L // 2], rng.integers(0, L, size=n_rows)]))
-    O, LSE, dQ = A.attn_query_rows(Q, K_, V, dO, rows, bag.scale)
+    O, LSE, dQ = A.attn_query_rows(Q, K_, V, dO, rows, bag.scale, causal)
     err_out = np.abs(run.host("out", sl, h)[rows] - O)
     err_out = np.where(err_out <= 2.0 ** -8 * np.abs(O), 0.0, err_out)     # bf16 resolution of the stored output
     e_out = float(np.max(err_out))
@@ -232,7 +232,7 @@ def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0):
     assert e_out <= FWD_TOL and e_lse <= LSE_TOL and e_dq <= BWD_TOL, msg
     if n_cols:
         cols = np.unique(np.concatenate([[0, L - 1], rng.integers(0, L, size=n_cols)]))
-        dKc, dVc = A.attn_key_cols(Q, K_, V, dO, cols, bag.scale)
+        dKc, dVc = A.attn_key_cols(Q, K_, V, dO, cols, bag.scale, causal)
         e_dk = rel_fro(run.host("dk", sl, h)[cols], dKc)
         e_dv = rel_fro(run.host("dv", sl, h)[cols], dVc)
         msg += f" dk={e_dk:.3e} dv={e_dv:.3e}"
@@ -307,5 +307,76 @@ def test_post_ulysses_share_sampled():
     _sampled_compare(run, 0, 1, n_rows=40)                  # 131072 tokens: query rows
     _sampled_compare(run, 1, 2, n_rows=40, n_cols=32)       # 32768 tokens: query rows and key rows
     _sampled_compare(run, 3, 0, n_rows=40, n_cols=32)       # 8192 tokens
+    for s in range(len(bag.seq_lens)):
+        _invariants(run, s, s % 3)
+
+
+# ---------------------------------------------------------------------------
+# Causal entry points (the second mask of the paper's Limitations paragraph):
+# the same bars against the oracle's causal mode.  The first rows of a causal
+# sequence see one or two keys and return single v entries, hence strict_fwd=False.
+# ---------------------------------------------------------------------------
+
+def test_causal_tiny_bag_full_oracle():
+    _full_compare(config_bag(0), strict_fwd=False, causal=True)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_causal_ragged_lengths_around_every_tile_boundary(d):
+    # query tiles are 128 rows, key tiles 64 / 128: lengths on both sides of each multiple, pairs of
+    # tiles with and without a middle tile (odd and even tile counts), zero-length and 1-token sequences
+    lens = [1, 2, 63, 64, 65, 0, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 385, 513, 640, 1]
+    run = _full_compare(BagSpec("causal_ragged", lens, H=3, d=d, seed=1777 + d), strict_fwd=False, causal=True)
+    assert np.all(np.isfinite(to_f64(run.out_bits))) and np.all(np.isfinite(run.lse))
+
+
+def test_causal_long_sequences_many_tile_pairs():
+    _full_compare(BagSpec("causal_long", [2500, 1111, 77], H=2, d=128, seed=5252), strict_fwd=False, causal=True)
+
+
+def test_causal_many_short_sequences():
+    rng = np.random.default_rng(199)
+    lens = [int(x) for x in rng.integers(1, 200, size=150)]
+    _full_compare(BagSpec("causal_short", lens, H=2, d=64, seed=5353), strict_fwd=False, causal=True)
+
+
+def test_causal_first_row_returns_its_own_value_and_differs_from_full():
+    """Row 0 of every sequence sees one key: out = v bit for bit, lse = scale q.k; and the causal
+    result is not the bidirectional one."""
+    bag = BagSpec("causal_row0", [300, 41, 129], H=2, d=128, seed=5454)
+    run_c = GpuRun(bag, backward=False, causal=True)
+    run_f = GpuRun(bag, backward=False)
+    cu = [int(c) for c in run_c.cu]
+    for s in range(len(bag.seq_lens)):
+        r = cu[s]
+        assert np.array_equal(run_c.out_bits[r], run_c.bits["v"][r])
+        for h in range(bag.H):
+            want = bag.scale * float(to_f64(run_c.bits["q"][r, h]) @ to_f64(run_c.bits["k"][r, h]))
+            assert abs(run_c.lse[h, r] - want) <= 1e-3
+    assert np.max(np.abs(to_f64(run_c.out_bits) - to_f64(run_f.out_bits))) > 0.1
+
+
+@pytest.mark.timeout(300)
+def test_causal_mixed_res_image_bag_sampled():
+    """Benchmark config 1 at full size under the causal mask: sampled query rows and key rows."""
+    bag = config_bag(1)
+    run = GpuRun(bag, causal=True)
+    longest = int(np.argmax(bag.seq_lens))
+    shortest = int(np.argmin(bag.seq_lens))
+    _sampled_compare(run, longest, 3, n_rows=48, n_cols=48, causal=True)
+    _sampled_compare(run, shortest, 20, n_rows=48, n_cols=48, causal=True)
+    _sampled_compare(run, 1, 12, n_rows=32, n_cols=16, causal=True)
+    for s in (longest, shortest):
+        _invariants(run, s, 7)          # rows of P still sum to one; <Q,dQ> = <K,dK>
+
+
+@pytest.mark.timeout(300)
+def test_causal_post_ulysses_share_sampled():
+    """Benchmark config 4 at full size under the causal mask (131072-token sequence, 512 tile pairs)."""
+    bag = config_bag(4)
+    run = GpuRun(bag, causal=True)
+    _sampled_compare(run, 0, 1, n_rows=40, causal=True)
+    _sampled_compare(run, 1, 2, n_rows=40, n_cols=32, causal=True)
+    _sampled_compare(run, 3, 0, n_rows=40, n_cols=32, causal=True)
     for s in range(len(bag.seq_lens)):
         _invariants(run, s, s % 3)
