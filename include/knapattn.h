@@ -115,6 +115,51 @@ int knap_varlen_attn_causal_bwd(const void* q, const void* k, const void* v,
                                 void* workspace, size_t workspace_bytes,
                                 void* stream);
 
+/* ------------------------------------------------------------------------
+ * Local data movement of the Ulysses layout switch (Sec. 3.4).  A g-GPU bag
+ * goes from (partial sequences, full heads) to (full sequences, partial heads)
+ * with one all-to-all before attention and back with one after it.  Around
+ * each all-to-all (which is the caller's, e.g. RCCL) every GPU of the bag
+ * rearranges its own data so that what it sends to one peer is contiguous.
+ * Element type: any two-byte type (bf16); (H / g) * d must be a multiple of 8
+ * so that a (token, head-group) row is a whole number of 16-byte units.
+ * Device pointers, 16-byte aligned, caller-owned; in and out must not alias;
+ * nothing allocates or synchronises; a tensor may hold at most 2^31 units.
+ *
+ * Layouts.  GPU r of the bag holds chunk r of every sequence of the bag (second
+ * pass of Sec. 3.3: g contiguous chunks as even as possible, the first L mod g
+ * one token longer), packed in the bag's sequence order: (T_r, H, d).
+ *   pack_heads    x (T_r, H, d) -> y (g, T_r, H/g, d); slab r' = heads
+ *                 [r' H/g, (r'+1) H/g) of every local token = what GPU r' gets.
+ *   unpack_heads  the inverse (after the second all-to-all).
+ * After the first all-to-all a GPU holds g slabs, from GPU 0 .. g-1 in that
+ * order, slab r being (T_r, H/g, d): `recv`, T = sum_r T_r rows in all.
+ *   gather_chunks   recv -> z (T, H/g, d), every sequence whole and in the
+ *                   bag's order (the input of knap_varlen_attn_* with H/g heads
+ *                   and the bag's cu_seqlens).
+ *   scatter_chunks  the inverse (before the second all-to-all).
+ * Both use row_map (int32[T], device): z[t] = recv[row_map[t]].  It depends
+ * only on the bag's cu_seqlens and g; knap_ulysses_plan builds it on the device
+ * (workspace: knap_ulysses_plan_workspace_bytes(n_seq, g) bytes of scratch, free
+ * to reuse once the plan kernels have run) and it serves q, k, v, the attention
+ * output and their gradients in every layer until the bag changes.
+ * ------------------------------------------------------------------------ */
+#define KNAP_ULYSSES_MAX_GPUS 64
+
+int knap_ulysses_pack_heads(const void* x, int64_t local_tokens, int H, int d, int g, void* y, void* stream);
+int knap_ulysses_unpack_heads(const void* y, int64_t local_tokens, int H, int d, int g, void* x, void* stream);
+
+size_t knap_ulysses_plan_workspace_bytes(int n_seq, int g);
+/* cu_seqlens: device int32[n_seq + 1] of the WHOLE sequences of the bag;
+ * total_tokens must equal cu_seqlens[n_seq]; 1 <= g <= KNAP_ULYSSES_MAX_GPUS. */
+int knap_ulysses_plan(const int32_t* cu_seqlens, int n_seq, int64_t total_tokens, int g,
+                      int32_t* row_map, void* workspace, size_t workspace_bytes, void* stream);
+
+int knap_ulysses_gather_chunks(const void* recv, const int32_t* row_map, int64_t total_tokens,
+                               int heads_local, int d, void* z, void* stream);
+int knap_ulysses_scatter_chunks(const void* z, const int32_t* row_map, int64_t total_tokens,
+                                int heads_local, int d, void* send, void* stream);
+
 /* Message for a KNAP_ERR_* code (static string, never NULL). */
 const char* knap_strerror(int code);
 
@@ -172,6 +217,11 @@ int knap_greedy_assign_weights(const double* weight, int n_seq,
 /* Second pass (Sec. 3.3): lengths of the g contiguous chunks of a sequence,
  * the first (L mod g) one token longer.  Writes chunk_len[g]. */
 int knap_chunk_lengths(int64_t L, int g, int64_t* chunk_len);
+
+/* Tokens every GPU of a g-GPU bag holds after the second pass: tokens_of_gpu[r] =
+ * sum over the bag's sequences of the length of chunk r (the T_r above, and the
+ * split sizes of the all-to-all).  Writes tokens_of_gpu[g]. */
+int knap_ulysses_local_tokens(const int64_t* seq_len, int n_seq, int g, int64_t* tokens_of_gpu);
 
 /* Workload imbalance ratio (Sec. 4.2): max / min over bags of load_j / gpus_j. */
 double knap_wir(const double* bag_load, const int* bag_gpus, int n_bags);

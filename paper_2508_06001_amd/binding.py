@@ -22,6 +22,7 @@ KNAP_ERR_TOO_MANY_SEQS = -4
 KNAP_ERR_CAPACITY = -5
 KNAP_ERR_PARSE = -6
 KNAP_MAX_SEQS = 2048
+KNAP_ULYSSES_MAX_GPUS = 64
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -45,6 +46,13 @@ _SIGNATURES = {
     "knap_varlen_attn_bwd_workspace_bytes": (_sz, [_i64, _i, _i, _i]),
     "knap_varlen_attn_causal_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp]),
     "knap_varlen_attn_causal_bwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "knap_ulysses_pack_heads": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp]),
+    "knap_ulysses_unpack_heads": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp]),
+    "knap_ulysses_plan_workspace_bytes": (_sz, [_i, _i]),
+    "knap_ulysses_plan": (_i, [_vp, _i, _i64, _i, _vp, _vp, _sz, _vp]),
+    "knap_ulysses_gather_chunks": (_i, [_vp, _vp, _i64, _i, _i, _vp, _vp]),
+    "knap_ulysses_scatter_chunks": (_i, [_vp, _vp, _i64, _i, _i, _vp, _vp]),
+    "knap_ulysses_local_tokens": (_i, [_pi64, _i, _i, _pi64]),
     "knap_strerror": (C.c_char_p, [_i]),
     "knap_last_hip_error": (_i, []),
     "knap_launch_workgroups": (_i, [_i]),
@@ -165,6 +173,66 @@ def knap_bwd_profile_events(start: Optional[int], stop: Optional[int]) -> None:
 
 def knap_launch_workgroups(which: int) -> int:
     return int(lib.knap_launch_workgroups(which))
+
+
+# --------------------------------------------------------------------------- Ulysses layout switch (local part)
+
+def knap_ulysses_pack_heads(x, local_tokens: int, H: int, d: int, g: int, y, stream=None, check: bool = True) -> int:
+    """x (T_r, H, d) -> y (g, T_r, H/g, d); CUDA tensors of a two-byte type."""
+    rc = lib.knap_ulysses_pack_heads(_ptr(x), local_tokens, H, d, g, _ptr(y), _stream_handle(stream))
+    if check:
+        _check(rc, "knap_ulysses_pack_heads")
+    return rc
+
+
+def knap_ulysses_unpack_heads(y, local_tokens: int, H: int, d: int, g: int, x, stream=None, check: bool = True) -> int:
+    rc = lib.knap_ulysses_unpack_heads(_ptr(y), local_tokens, H, d, g, _ptr(x), _stream_handle(stream))
+    if check:
+        _check(rc, "knap_ulysses_unpack_heads")
+    return rc
+
+
+def knap_ulysses_plan_workspace_bytes(n_seq: int, g: int) -> int:
+    return int(lib.knap_ulysses_plan_workspace_bytes(n_seq, g))
+
+
+def knap_ulysses_plan(cu_seqlens, n_seq: int, total_tokens: int, g: int, row_map, workspace,
+                      workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    """Fills row_map (int32 CUDA tensor of total_tokens entries) for a g-GPU bag."""
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.knap_ulysses_plan(_ptr(cu_seqlens), n_seq, total_tokens, g, _ptr(row_map), _ptr(workspace),
+                               workspace_bytes, _stream_handle(stream))
+    if check:
+        _check(rc, "knap_ulysses_plan")
+    return rc
+
+
+def knap_ulysses_gather_chunks(recv, row_map, total_tokens: int, heads_local: int, d: int, z,
+                               stream=None, check: bool = True) -> int:
+    rc = lib.knap_ulysses_gather_chunks(_ptr(recv), _ptr(row_map), total_tokens, heads_local, d, _ptr(z),
+                                        _stream_handle(stream))
+    if check:
+        _check(rc, "knap_ulysses_gather_chunks")
+    return rc
+
+
+def knap_ulysses_scatter_chunks(z, row_map, total_tokens: int, heads_local: int, d: int, send,
+                                stream=None, check: bool = True) -> int:
+    rc = lib.knap_ulysses_scatter_chunks(_ptr(z), _ptr(row_map), total_tokens, heads_local, d, _ptr(send),
+                                         _stream_handle(stream))
+    if check:
+        _check(rc, "knap_ulysses_scatter_chunks")
+    return rc
+
+
+def knap_ulysses_local_tokens(seq_lens, g: int):
+    """T_r for r = 0..g-1: tokens every GPU of a g-GPU bag holds after the second pass."""
+    n = len(seq_lens)
+    arr = (C.c_int64 * max(n, 1))(*[int(x) for x in seq_lens])
+    out = (C.c_int64 * g)()
+    _check(lib.knap_ulysses_local_tokens(arr, n, g, out), "knap_ulysses_local_tokens")
+    return [int(v) for v in out]
 
 
 # --------------------------------------------------------------------------- host model / balancer

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libknapattn.so")
 
-HIP_SOURCES = ["knap_attn_fwd.hip", "knap_attn_bwd.hip", "knap_api.hip"]
+HIP_SOURCES = ["knap_attn_fwd.hip", "knap_attn_bwd.hip", "knap_ulysses.hip", "knap_api.hip"]
 C_SOURCES = ["knap_host.c"]
 
 HIP_FLAGS = [

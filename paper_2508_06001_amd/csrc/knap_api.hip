@@ -170,6 +170,92 @@ int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
 
 extern "C" {
 
+// ---------------------------------------------------------------------------
+// Ulysses layout switch: local data movement
+// ---------------------------------------------------------------------------
+
+namespace {
+
+// 16-byte units per row of `heads` heads of d two-byte elements; 0 if the row is not a whole number of units
+uint64_t row_units(int heads, int d) {
+  const uint64_t bytes = (uint64_t)heads * (uint64_t)d * 2u;
+  return bytes % 16u ? 0u : bytes / 16u;
+}
+
+int ulysses_heads(const void* src, void* dst, int64_t local_tokens, int H, int d, int g, bool pack, void* stream) {
+  if (local_tokens < 0 || H <= 0 || d <= 0 || g <= 0 || H % g != 0) return KNAP_ERR_INVALID_ARG;
+  const uint64_t U = row_units(H / g, d);
+  if (U == 0) return KNAP_ERR_INVALID_ARG;
+  if (local_tokens == 0) return KNAP_OK;
+  if ((uint64_t)local_tokens * g * U > (1ull << 31)) return KNAP_ERR_INVALID_ARG;
+  if (!src || !dst || src == dst || !aligned(src, 16) || !aligned(dst, 16)) return KNAP_ERR_INVALID_ARG;
+  DeviceInfo* di = device_info();
+  if (!di) return KNAP_ERR_LAUNCH_FAILED;
+  const hipError_t e = knap::launch_ulysses_heads(src, dst, (uint32_t)local_tokens, (uint32_t)U, (uint32_t)g, pack,
+                                                  di->cus, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
+  return KNAP_OK;
+}
+
+int ulysses_rows(const void* src, void* dst, const int32_t* row_map, int64_t total_tokens, int heads_local, int d,
+                 bool gather, void* stream) {
+  if (total_tokens < 0 || heads_local <= 0 || d <= 0) return KNAP_ERR_INVALID_ARG;
+  const uint64_t U = row_units(heads_local, d);
+  if (U == 0) return KNAP_ERR_INVALID_ARG;
+  if (total_tokens == 0) return KNAP_OK;
+  if ((uint64_t)total_tokens * U > (1ull << 31)) return KNAP_ERR_INVALID_ARG;
+  if (!src || !dst || !row_map || src == dst || !aligned(src, 16) || !aligned(dst, 16) || !aligned(row_map, 4))
+    return KNAP_ERR_INVALID_ARG;
+  DeviceInfo* di = device_info();
+  if (!di) return KNAP_ERR_LAUNCH_FAILED;
+  const hipError_t e = knap::launch_ulysses_rows(src, dst, row_map, (uint32_t)total_tokens, (uint32_t)U, gather,
+                                                 di->cus, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
+  return KNAP_OK;
+}
+
+}  // namespace
+
+int knap_ulysses_pack_heads(const void* x, int64_t local_tokens, int H, int d, int g, void* y, void* stream) {
+  return ulysses_heads(x, y, local_tokens, H, d, g, true, stream);
+}
+
+int knap_ulysses_unpack_heads(const void* y, int64_t local_tokens, int H, int d, int g, void* x, void* stream) {
+  return ulysses_heads(y, x, local_tokens, H, d, g, false, stream);
+}
+
+size_t knap_ulysses_plan_workspace_bytes(int n_seq, int g) {
+  if (n_seq < 0 || g <= 0) return 0;
+  return round_up((static_cast<size_t>(n_seq) + 1) * static_cast<size_t>(g) * sizeof(int32_t), 256);
+}
+
+int knap_ulysses_plan(const int32_t* cu_seqlens, int n_seq, int64_t total_tokens, int g,
+                      int32_t* row_map, void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_seq < 0 || g <= 0 || g > KNAP_ULYSSES_MAX_GPUS || total_tokens < 0 || total_tokens > INT32_MAX)
+    return KNAP_ERR_INVALID_ARG;
+  if (n_seq > KNAP_MAX_SEQS) return KNAP_ERR_TOO_MANY_SEQS;
+  if (n_seq == 0 || total_tokens == 0) return KNAP_OK;
+  if (!cu_seqlens || !row_map || !workspace || !aligned(cu_seqlens, 4) || !aligned(row_map, 4) ||
+      !aligned(workspace, 4))
+    return KNAP_ERR_INVALID_ARG;
+  if (workspace_bytes < knap_ulysses_plan_workspace_bytes(n_seq, g)) return KNAP_ERR_WORKSPACE_TOO_SMALL;
+  const hipError_t e = knap::launch_ulysses_plan(cu_seqlens, n_seq, g, (int)total_tokens,
+                                                 static_cast<int32_t*>(workspace), row_map,
+                                                 static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
+  return KNAP_OK;
+}
+
+int knap_ulysses_gather_chunks(const void* recv, const int32_t* row_map, int64_t total_tokens,
+                               int heads_local, int d, void* z, void* stream) {
+  return ulysses_rows(recv, z, row_map, total_tokens, heads_local, d, true, stream);
+}
+
+int knap_ulysses_scatter_chunks(const void* z, const int32_t* row_map, int64_t total_tokens,
+                                int heads_local, int d, void* send, void* stream) {
+  return ulysses_rows(z, send, row_map, total_tokens, heads_local, d, false, stream);
+}
+
 const char* knap_strerror(int code) {
   switch (code) {
     case KNAP_OK: return "success";

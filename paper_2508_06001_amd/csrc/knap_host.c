@@ -172,6 +172,17 @@ int knap_chunk_lengths(int64_t L, int g, int64_t* chunk_len) {
   return KNAP_OK;
 }
 
+int knap_ulysses_local_tokens(const int64_t* seq_len, int n_seq, int g, int64_t* tokens_of_gpu) {
+  if (n_seq < 0 || g <= 0 || !tokens_of_gpu || (n_seq > 0 && !seq_len)) return KNAP_ERR_INVALID_ARG;
+  for (int r = 0; r < g; ++r) tokens_of_gpu[r] = 0;
+  for (int s = 0; s < n_seq; ++s) {
+    if (seq_len[s] < 0) return KNAP_ERR_INVALID_ARG;
+    const int64_t base = seq_len[s] / g, rem = seq_len[s] % g;
+    for (int r = 0; r < g; ++r) tokens_of_gpu[r] += base + (r < rem ? 1 : 0);
+  }
+  return KNAP_OK;
+}
+
 double knap_wir(const double* bag_load, const int* bag_gpus, int n_bags) {
   if (!bag_load || !bag_gpus || n_bags <= 0) return NAN;
   double hi = 0.0, lo = 0.0;

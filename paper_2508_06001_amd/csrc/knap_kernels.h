@@ -21,6 +21,15 @@ hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t
                       int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop);
 
+// Ulysses layout switch, local data movement; rows of U 16-byte units.
+hipError_t launch_ulysses_heads(const void* src, void* dst, uint32_t T, uint32_t U, uint32_t g, bool pack,
+                                int cus, hipStream_t stream);
+hipError_t launch_ulysses_rows(const void* src, void* dst, const int32_t* row_map, uint32_t T, uint32_t U,
+                               bool gather, int cus, hipStream_t stream);
+// table: (n_seq + 1) g ints of scratch
+hipError_t launch_ulysses_plan(const int32_t* cu, int n_seq, int g, int T, int32_t* table, int32_t* row_map,
+                               hipStream_t stream);
+
 // resident workgroups per compute unit of the persistent kernels
 int fwd_workgroups_per_cu(int d);
 int bwd_dkdv_workgroups_per_cu(int d);

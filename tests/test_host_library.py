@@ -118,3 +118,28 @@ def test_chunks_wir_and_fit():
         K.knap_fit_cost_model([1.0], [1.0], [1.0])
     with pytest.raises(K.KnapError):
         K.knap_fit_cost_model([1.0, 2.0], [1.0, 2.0], [1.0, 0.0])
+
+
+def test_ulysses_host_side_and_argument_checks():
+    """Chunk bookkeeping of a multi-GPU bag against the oracle, and argument errors of the device entry
+    points that are decided before anything touches a GPU."""
+    from oracle import ulysses as U
+    rng = np.random.default_rng(3)
+    for g in (1, 2, 3, 8):
+        lens = [int(v) for v in rng.integers(0, 5000, size=17)] + [0, 1, g - 1, g, g + 1]
+        assert K.knap_ulysses_local_tokens(lens, g) == [U.local_tokens(lens, g, r) for r in range(g)]
+        assert sum(K.knap_ulysses_local_tokens(lens, g)) == sum(lens)
+    assert K.knap_ulysses_plan_workspace_bytes(10, 8) >= 11 * 8 * 4
+    assert K.knap_ulysses_plan_workspace_bytes(-1, 8) == 0
+    bad = K.KNAP_ERR_INVALID_ARG
+    # H not divisible by g; a (token, head-group) row that is not a whole number of 16-byte units; g < 1
+    assert K.lib.knap_ulysses_pack_heads(None, 16, 6, 64, 4, None, None) == bad
+    assert K.lib.knap_ulysses_pack_heads(None, 16, 4, 4, 4, None, None) == bad
+    assert K.lib.knap_ulysses_unpack_heads(None, 16, 8, 64, 0, None, None) == bad
+    assert K.lib.knap_ulysses_gather_chunks(None, None, -1, 3, 128, None, None) == bad
+    assert K.lib.knap_ulysses_plan(None, 4, 100, K.KNAP_ULYSSES_MAX_GPUS + 1, None, None, 0, None) == bad
+    assert K.lib.knap_ulysses_plan(None, K.KNAP_MAX_SEQS + 1, 100, 8, None, None, 0, None) == K.KNAP_ERR_TOO_MANY_SEQS
+    # nothing to do: success without pointers
+    assert K.lib.knap_ulysses_pack_heads(None, 0, 8, 64, 4, None, None) == K.KNAP_OK
+    assert K.lib.knap_ulysses_scatter_chunks(None, None, 0, 3, 128, None, None) == K.KNAP_OK
+    assert K.lib.knap_ulysses_plan(None, 0, 0, 8, None, None, 0, None) == K.KNAP_OK
