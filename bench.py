@@ -443,6 +443,128 @@ def run_fit(args):
     print(json.dumps({"fit_report": path}), flush=True)
 
 
+def run_ulysses(args):
+    """Data movement around the Ulysses all-to-alls (Sec. 3.4) for one GPU of the 8-GPU bag whose
+    post-switch share is benchmark config 4: a step = what one attention layer costs this GPU locally,
+    forward direction: pack_heads + gather_chunks for q, k and v, then scatter_chunks + unpack_heads for
+    the attention output (8 kernels, each reading and writing one (tokens, heads, d) bf16 tensor once)."""
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import config_bag, cu_seqlens_of
+
+    bag = config_bag(4)
+    seq_lens = bag.seq_lens
+    g, H, d = 8, 24, 128
+    hg, T = H // g, sum(seq_lens)
+    T_r = K.knap_ulysses_local_tokens(seq_lens, g)[0]
+    log(f"[ulysses] bag of {g} GPUs: n_seq={len(seq_lens)} T={T} H={H} d={d}; this GPU holds {T_r} tokens x {H} heads "
+        f"before the switch and {T} tokens x {hg} heads after it")
+    gen = torch.Generator(device="cuda").manual_seed(20250810)
+    mk = lambda *shape: torch.randint(-32768, 32767, shape, dtype=torch.int16, device="cuda", generator=gen)
+    xs = [mk(T_r, H, d) for _ in range(3)]                 # q, k, v before the switch
+    ys = [torch.empty((g, T_r, hg, d), dtype=torch.int16, device="cuda") for _ in range(3)]
+    recvs = [mk(T, hg, d) for _ in range(3)]               # what the all-to-all delivers (stand-in values)
+    zs = [torch.empty((T, hg, d), dtype=torch.int16, device="cuda") for _ in range(3)]
+    # attention output, (full sequences, partial heads), and its way back; three sets as well, so that the
+    # per-kernel timings below can rotate over 0.9 GB and never find their data in the 256 MB Infinity Cache
+    o_fulls = [mk(T, hg, d) for _ in range(3)]
+    o_sends = [torch.empty((T, hg, d), dtype=torch.int16, device="cuda") for _ in range(3)]
+    o_recvs = [mk(g, T_r, hg, d) for _ in range(3)]
+    o_locs = [torch.empty((T_r, H, d), dtype=torch.int16, device="cuda") for _ in range(3)]
+    o_full, o_send, o_recv, o_loc = o_fulls[0], o_sends[0], o_recvs[0], o_locs[0]
+    cu = torch.tensor(cu_seqlens_of(seq_lens), dtype=torch.int32, device="cuda")
+    row_map = torch.empty((T,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(K.knap_ulysses_plan_workspace_bytes(len(seq_lens), g), dtype=torch.uint8, device="cuda")
+    K.knap_ulysses_plan(cu, len(seq_lens), T, g, row_map, ws)
+    torch.cuda.synchronize()
+    tensor_bytes = T_r * H * d * 2
+    assert tensor_bytes == T * hg * d * 2
+
+    def step():
+        for x, y, r, z in zip(xs, ys, recvs, zs):
+            K.knap_ulysses_pack_heads(x, T_r, H, d, g, y)
+            K.knap_ulysses_gather_chunks(r, row_map, T, hg, d, z)
+        K.knap_ulysses_scatter_chunks(o_full, row_map, T, hg, d, o_send)
+        K.knap_ulysses_unpack_heads(o_recv, T_r, H, d, g, o_loc)
+
+    ev = HipEvents()
+    stream = int(torch.cuda.current_stream().cuda_stream)
+
+    def timed(fn, n):
+        a, b = ev.create(), ev.create()
+        ev.record(a, stream)
+        for _ in range(n):
+            fn()
+        ev.record(b, stream)
+        torch.cuda.synchronize()
+        ms = ev.elapsed_ms(a, b) / n
+        ev.destroy(a); ev.destroy(b)
+        return ms
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ms = timed(step, args.steps)
+    step_bytes = 8 * 2 * tensor_bytes                       # every kernel reads and writes one tensor
+    value = step_bytes / (ms * 1e-3) / 1e9
+    def rotating(call, *sets):
+        state = {"i": 0}
+
+        def fn():
+            i = state["i"] % 3
+            state["i"] += 1
+            call(*(s_[i] for s_ in sets))
+        return fn
+
+    n_k = 6 * args.steps
+    per_kernel = {
+        "pack_heads": timed(rotating(lambda x, y: K.knap_ulysses_pack_heads(x, T_r, H, d, g, y), xs, ys), n_k),
+        "gather_chunks": timed(rotating(lambda r, z: K.knap_ulysses_gather_chunks(r, row_map, T, hg, d, z), recvs, zs), n_k),
+        "scatter_chunks": timed(rotating(lambda z, s_: K.knap_ulysses_scatter_chunks(z, row_map, T, hg, d, s_), o_fulls, o_sends), n_k),
+        "unpack_heads": timed(rotating(lambda y, x: K.knap_ulysses_unpack_heads(y, T_r, H, d, g, x), o_recvs, o_locs), n_k),
+        "plain_device_copy": timed(rotating(lambda a, b: b.copy_(a), o_fulls, o_sends), n_k),
+        "plan (once per bag)": timed(lambda: K.knap_ulysses_plan(cu, len(seq_lens), T, g, row_map, ws), args.steps),
+    }
+    gbps = {k: (2 * tensor_bytes / (v * 1e-3) / 1e9 if "plan" not in k else None) for k, v in per_kernel.items()}
+    for k, v in per_kernel.items():
+        log(f"[ulysses] {k}: {v * 1e3:.1f} us" + (f", {gbps[k]:.0f} GB/s" if gbps[k] else ""))
+    slow = max(("pack_heads", "gather_chunks", "scatter_chunks", "unpack_heads"), key=lambda k: per_kernel[k])
+    out = {
+        "metric": "Ulysses local data movement GB/s (1 GPU of an 8-GPU bag)", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": "8-GPU bag of configs[4]: pre_attn for q, k, v + post_attn for the output, one GPU's share",
+                   "bag_gpus": g, "H": H, "d": d, "tokens_before_switch": T_r, "tokens_after_switch": T,
+                   "bytes_per_step": step_bytes, "kernels_per_step": 8},
+        "kernel_us": {k: round(v * 1e3, 2) for k, v in per_kernel.items()},
+        "kernel_gbps": {k: (round(v, 1) if v else None) for k, v in gbps.items()},
+        "roofline": {"bound": "hbm", "kernel": slow, "achieved": round(gbps[slow], 1), "peak": 8000.0, "unit": "GB/s",
+                     "frac": round(gbps[slow] / 8000.0, 4), "avg_launch_ms": round(per_kernel[slow], 5),
+                     "bytes_per_launch": 2 * tensor_bytes,
+                     "traffic": measured_traffic("ulysses 8-GPU bag of configs[4]",
+                                                 {"pack_heads": "ulysses_heads_kernel<true>", "unpack_heads": "ulysses_heads_kernel<false>",
+                                                  "gather_chunks": "ulysses_rows_kernel<true>",
+                                                  "scatter_chunks": "ulysses_rows_kernel<false>"}[slow])},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import ulysses as U
+        n_tok = 4096                                        # a sample of this GPU's tokens
+        xh = np.random.default_rng(1).integers(0, 1 << 16, size=(n_tok, H, d), dtype=np.uint16)
+        lens = [n_tok // 4] * 4
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < min(args.cpu_budget, 10.0):
+            yh = U.pack_heads(xh, g)
+            zh = U.gather_chunks(U.scatter_chunks(yh[0], lens, g), lens)
+            reps += 1
+        dt = time.perf_counter() - t0
+        moved = reps * 2 * (xh.nbytes + 2 * yh[0].nbytes)   # pack: whole tensor; scatter + gather: one slab each
+        out["cpu_baseline"] = {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{reps} x (pack_heads of {n_tok} tokens x {H} heads + scatter/gather of one slab), numpy"}
+        log(f"[ulysses] cpu oracle: {out['cpu_baseline']['value']:.2f} GB/s ({out['cpu_baseline']['sample']})")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -454,6 +576,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
+    ap.add_argument("--ulysses", action="store_true",
+                    help="time the local data movement around the Ulysses all-to-alls (not the headline workload)")
     ap.add_argument("--fit-draws", type=int, default=12, help="evaluation bags per benchmark configuration in --fit")
     ap.add_argument("--fit-preheat", type=float, default=10.0, help="seconds of load before the calibration in --fit")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -470,6 +594,8 @@ def main():
     torch.cuda.set_device(0)
     if args.fit:
         run_fit(args)
+    elif args.ulysses:
+        run_ulysses(args)
     else:
         run_default(args)
 

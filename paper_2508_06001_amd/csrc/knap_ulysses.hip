@@ -19,7 +19,14 @@ namespace {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kCopyThreads = 256;
-constexpr int kUnroll = 4;          // 16-byte units per thread and loop trip: 64 bytes in flight per lane
+// Tuned on an MI355X (one (24576, 24, 128) bf16 tensor, buffers rotated out of the Infinity Cache):
+// non-temporal loads and stores +12 % over plain ones, 32 workgroups per CU +4 % over 16, two units per
+// thread and trip as good as four or eight; 5.7 TB/s against 5.3 TB/s of the runtime's device copy.
+constexpr int kUnroll = 2;           // 16-byte units per thread and loop trip
+constexpr int kWorkgroupsPerCu = 32; // grid cap; beyond it the kernels loop with a grid stride
+
+__device__ __forceinline__ u32x4_t ld_unit(const u32x4_t* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st_unit(u32x4_t* p, u32x4_t v) { __builtin_nontemporal_store(v, p); }
 
 // y[(r T + t) U + c] = x[(t g + r) U + c]: U units per (token, head-group) row.  Iterates over x's
 // linear index, so x is touched in address order and y in runs of U units.
@@ -43,10 +50,10 @@ __global__ __launch_bounds__(kCopyThreads) void ulysses_heads_kernel(
     }
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
-      if (xi[k] < N) val[k] = src[PACK ? xi[k] : yi[k]];
+      if (xi[k] < N) val[k] = ld_unit(&src[PACK ? xi[k] : yi[k]]);
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
-      if (xi[k] < N) dst[PACK ? yi[k] : xi[k]] = val[k];
+      if (xi[k] < N) st_unit(&dst[PACK ? yi[k] : xi[k]], val[k]);
   }
 }
 
@@ -69,10 +76,10 @@ __global__ __launch_bounds__(kCopyThreads) void ulysses_rows_kernel(
     }
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
-      if (zi[k] < N) val[k] = src[GATHER ? mi[k] : zi[k]];
+      if (zi[k] < N) val[k] = ld_unit(&src[GATHER ? mi[k] : zi[k]]);
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k)
-      if (zi[k] < N) dst[GATHER ? zi[k] : mi[k]] = val[k];
+      if (zi[k] < N) st_unit(&dst[GATHER ? zi[k] : mi[k]], val[k]);
   }
 }
 
@@ -137,7 +144,7 @@ __global__ __launch_bounds__(kCopyThreads) void ulysses_row_map_kernel(
 int copy_grid(uint64_t units, int cus) {
   const uint64_t per_wg = (uint64_t)kCopyThreads * kUnroll;
   const uint64_t want = (units + per_wg - 1) / per_wg;
-  const uint64_t cap = (uint64_t)cus * 16;       // enough waves to cover the memory latency, then a grid-stride loop
+  const uint64_t cap = (uint64_t)cus * kWorkgroupsPerCu;
   return (int)(want < cap ? (want ? want : 1) : cap);
 }
 
