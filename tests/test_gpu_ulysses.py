@@ -128,3 +128,61 @@ def test_post_ulysses_share_at_full_size():
     K.knap_ulysses_scatter_chunks(z, row_map, T, hg, d, send)
     torch.cuda.synchronize()
     assert np.array_equal(_host(send), recv)
+
+
+@pytest.mark.timeout(300)
+def test_multi_gpu_bag_end_to_end_on_one_gpu():
+    """Sec. 3.4 end to end for a 4-GPU bag, every rank simulated on the one GPU: q, k, v start as
+    (partial sequences, full heads); pack -> exchange -> gather -> packed attention on H/g heads ->
+    scatter -> exchange -> unpack.  What every rank ends with must be its chunks of the attention of
+    the whole sequences over all heads (fp64 oracle, the forward bars of the parity tests)."""
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import BagSpec, make_qkv_dout
+    from oracle import attention as A
+    from gpu_util import to_f64
+    g, H, d = 4, 8, 128
+    hg = H // g
+    bag = BagSpec("ulysses_e2e", [700, 130, 3, 257, 1024], H=H, d=d, seed=881)
+    seq_lens, T = bag.seq_lens, bag.total_tokens
+    bits = make_qkv_dout(bag)                                    # the unsplit packed tensors
+    cu = cu_seqlens_of(seq_lens)
+    row_map = _plan(K, seq_lens, g)
+    T_r = K.knap_ulysses_local_tokens(seq_lens, g)
+    # every rank packs its q, k, v
+    sent = {}
+    for name in ("q", "k", "v"):
+        local = U.split_to_ranks(bits[name], seq_lens, g)
+        for r in range(g):
+            y = torch.empty((g, T_r[r], hg, d), dtype=torch.int16, device="cuda")
+            K.knap_ulysses_pack_heads(_dev(local[r]), T_r[r], H, d, g, y)
+            torch.cuda.synchronize()
+            sent[name, r] = _host(y)
+    # every rank gathers whole sequences and attends with its H/g heads
+    out_send = []
+    for rp in range(g):
+        full = {}
+        for name in ("q", "k", "v"):
+            recv = _dev(np.concatenate([sent[name, r][rp] for r in range(g)], axis=0))
+            z = torch.empty((T, hg, d), dtype=torch.int16, device="cuda")
+            K.knap_ulysses_gather_chunks(recv, row_map, T, hg, d, z)
+            full[name] = z.view(torch.bfloat16)
+        attn = K.VarlenAttention(cu, hg, d, bag.scale)
+        attn.forward(full["q"], full["k"], full["v"])
+        send = torch.empty((T, hg, d), dtype=torch.int16, device="cuda")
+        K.knap_ulysses_scatter_chunks(attn.out.view(torch.int16), row_map, T, hg, d, send)
+        torch.cuda.synchronize()
+        out_send.append(np.split(_host(send), np.cumsum(T_r)[:-1], axis=0))     # slab r goes back to rank r
+    # every rank unpacks; compare with the oracle on the unsplit problem
+    f64 = {n: to_f64(bits[n]) for n in ("q", "k", "v")}
+    o_ref, _ = A.varlen_attn_fwd(f64["q"], f64["k"], f64["v"], cu, bag.scale)
+    ref_local = U.split_to_ranks(o_ref, seq_lens, g)
+    for r in range(g):
+        back = np.stack([out_send[rp][r] for rp in range(g)], axis=0)
+        x = torch.empty((T_r[r], H, d), dtype=torch.int16, device="cuda")
+        K.knap_ulysses_unpack_heads(_dev(back), T_r[r], H, d, g, x)
+        torch.cuda.synchronize()
+        err = np.abs(to_f64(_host(x)) - ref_local[r])
+        err = np.where(err <= 2.0 ** -8 * np.abs(ref_local[r]), 0.0, err)       # bf16 resolution of the stored output
+        say(f"[parity] ulysses end to end, rank {r}: max|err|={float(err.max()):.3e}")
+        assert float(err.max()) <= 1e-2
