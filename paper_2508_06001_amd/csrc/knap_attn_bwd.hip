@@ -120,9 +120,9 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
     const size_t head_off = (size_t)it.head * D;
     // CAUSAL: the item is the pair of key tiles {p, kv_tiles - 1 - p}, the one with more queries first
     const int kv_tiles = (L + C::BN - 1) / C::BN;
-    for (int sub = 0; sub < (CAUSAL ? 2 : 1); ++sub) {
+    int sub = 0;
+  second_tile_of_pair:;     // CAUSAL only: jumped back to once, from the end of the first tile
     const int kv_tile = !CAUSAL ? it.tile : sub == 0 ? it.tile : kv_tiles - 1 - it.tile;
-    if (CAUSAL && sub == 1 && kv_tile == it.tile) break;   // the middle tile of an odd count
     const int kv0 = kv_tile * C::BN;
     // queries this key tile meets: rows q_first .. L - 1 of the sequence; the walk below counts its
     // tiles and rows from q_first
@@ -332,7 +332,12 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
         if (kv < L)
           dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[nb][r] * out_scale);
       }
-    }   // sub
+    if constexpr (CAUSAL) {
+      if (sub == 0 && it.tile != kv_tiles - 1 - it.tile) {   // not the middle tile of an odd count
+        sub = 1;
+        goto second_tile_of_pair;
+      }
+    }
   }
 }
 
