@@ -407,3 +407,17 @@ def test_causal_repeatable_and_independent_of_other_sequences():
     for a, b in ((run.out_bits, run2.out_bits), (run.dq_bits, run2.dq_bits), (run.dk_bits, run2.dk_bits),
                  (run.dv_bits, run2.dv_bits)):
         assert np.array_equal(a[keep], b[5:5 + 1290])
+
+
+@pytest.mark.timeout(300)
+def test_random_bags_both_masks():
+    """A sweep of random small bags (log-uniform lengths 1..3000, 1..40 sequences, H in {1, 2, 5}, both head
+    dims, both masks), every output against the full oracle."""
+    rng = np.random.default_rng(20250812)
+    for i in range(14):
+        n_seq = int(rng.integers(1, 41))
+        lens = [int(np.exp(rng.uniform(0.0, np.log(3000.0)))) for _ in range(n_seq)]
+        if i % 3 == 0:
+            lens[int(rng.integers(0, n_seq))] = 0
+        bag = BagSpec(f"random{i}", lens, H=int(rng.choice([1, 2, 5])), d=int(rng.choice([64, 128])), seed=9100 + i)
+        _full_compare(bag, strict_fwd=False, causal=bool(i % 2))
