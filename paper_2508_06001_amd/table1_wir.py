@@ -1,0 +1,65 @@
+"""Workload-imbalance ratios of the paper's three simulator workloads (Sec. 4.1 / Table 1: low_res,
+mixed_res, joint on 32 GPUs) with and without the greedy balancer, computed by the library's host code
+(knap_flux_workload, knap_parse_topology, knap_greedy_assign_weights, knap_wir; gamma = 0.49,
+d_model = 3072 as in the table's caption) and printed beside the values the paper prints.
+
+    python -m paper_2508_06001_amd.table1_wir [--seeds N]
+
+Sequence lengths follow the paper's data codes: (R/16)^2 visual tokens per frame, F frames (F / 3.4 for
+clips), text ~ U{0..392}, one aspect multiplier U[0.96, 1.04] per batch.  The "mean" column uses 196 text
+tokens and no jitter; the "random" column is the median over N seeded streams.  The paper drew its own
+random streams, so single cells differ; its values come from tests/golden/table1_wir.txt.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+
+import numpy as np
+
+import paper_2508_06001_amd as K
+from knap_inputs import table1_streams
+
+D_MODEL, GAMMA = 3072, 0.49
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def wir(workload: str, topo: str, seed=None) -> float:
+    per_gpu = table1_streams(workload, seed)
+    if topo == "none":                      # every GPU keeps what its loader gave it
+        loads = [sum(K.knap_flux_workload(l, D_MODEL, GAMMA) for l in g) for g in per_gpu]
+        return K.knap_wir(loads, [1] * len(loads))
+    weights = [K.knap_flux_workload(l, D_MODEL, GAMMA) for g in per_gpu for l in g]
+    bags = K.knap_parse_topology(topo)
+    _, load = K.knap_greedy_assign_weights(weights, bags)
+    return K.knap_wir(load, bags)
+
+
+def printed_cells():
+    cells = {}
+    path = os.path.join(ROOT, "tests", "golden", "table1_wir.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            line = line.strip()
+            if line and not line.startswith("#"):
+                w, t, v = line.split()
+                cells[w, t] = float(v)
+    return cells
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--seeds", type=int, default=5)
+    args = ap.parse_args()
+    paper = printed_cells()
+    print("%-10s %-6s %8s %8s %10s" % ("workload", "bags", "paper", "mean", "random"))
+    for workload in ("low_res", "mixed_res", "joint"):
+        for topo in ("none", "g1n32", "g2n16", "g4n8", "g8n4"):
+            rnd = float(np.median([wir(workload, topo, s) for s in range(args.seeds)]))
+            p = paper.get((workload, topo))
+            print("%-10s %-6s %8s %8.2f %10.2f" % (workload, topo, "-" if p is None else "%.2f" % p,
+                                                    wir(workload, topo), rnd))
+
+
+if __name__ == "__main__":
+    main()

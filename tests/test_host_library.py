@@ -143,3 +143,17 @@ def test_ulysses_host_side_and_argument_checks():
     assert K.lib.knap_ulysses_pack_heads(None, 0, 8, 64, 4, None, None) == K.KNAP_OK
     assert K.lib.knap_ulysses_scatter_chunks(None, None, 0, 3, 128, None, None) == K.KNAP_OK
     assert K.lib.knap_ulysses_plan(None, 0, 0, 8, None, None, 0, None) == K.KNAP_OK
+
+
+def test_table1_wir_script_reproduces_the_printed_column():
+    """The user-facing reproduction (C balancer on the paper's data-code streams) stays in the bands of
+    the cells the paper prints (the paper drew its own random streams)."""
+    from paper_2508_06001_amd import table1_wir as T
+    printed = T.printed_cells()
+    assert len(printed) == 15
+    for (workload, topo), val in printed.items():
+        got = float(np.median([T.wir(workload, topo, s) for s in range(5)]))
+        if topo == "none":
+            assert 0.5 * val <= got <= 1.6 * val, (workload, topo, got, val)
+        else:
+            assert abs(got - val) <= (0.6 if topo == "g1n32" else 0.12), (workload, topo, got, val)
