@@ -84,5 +84,9 @@ int main() {
   run<28, 8, 4, 0, 4>("28 FMA + 8 EXP + 4 LDS (each read feeds 2)");
   run<28, 8, 4, 0, 8>("28 FMA + 8 EXP + 4 LDS (each read feeds 2)");
   run<36, 8, 0, 0, 4>("36 FMA + 8 EXP, no LDS");
+  // head dimension 64: the softmax arithmetic per MFMA doubles
+  run<72, 16, 8, 0, 8>("72 FMA + 16 EXP + 8 LDS (d = 64 mix)");
+  run<72, 16, 4, 0, 8>("72 FMA + 16 EXP + 4 LDS (d = 64, each read feeds 2)");
+  run<72, 16, 0, 0, 8>("72 FMA + 16 EXP, no LDS");
   return 0;
 }
