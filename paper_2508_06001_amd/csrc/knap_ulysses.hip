@@ -138,6 +138,8 @@ __global__ __launch_bounds__(kCopyThreads) void ulysses_row_map_kernel(
     r = rem + k / base;               // base > 0 here: i < L and the longer chunks are used up
     j = k - (r - rem) * base;
   }
+  // rows past cu[n_seq] (a total_tokens larger than the lengths add up to) must not index outside the table
+  r = min(max(r, 0), g - 1);
   row_map[t] = table[n_seq * g + r] + table[s * g + r] + j;
 }
 
