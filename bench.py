@@ -323,17 +323,20 @@ def run_fit(args):
         torch.cuda.empty_cache()
     # H12_d64: the same length distributions at another head count and head dimension (is the model's
     # form specific to the benchmark's shape?)
+    # H24_d128_causal: the benchmark's shape under the causal mask (Sec. 3.4 says the per-sequence model
+    # stays effective for other masks): same regressors sum L^2 and sum L, own a and b
     for fam, (H, d, tokens) in {"H24_d128": (24, 128, 65536), "H3_d128": (3, 128, 196608),
-                                "H12_d64": (12, 64, 65536)}.items():
+                                "H12_d64": (12, 64, 65536), "H24_d128_causal": (24, 128, 65536)}.items():
+        causal = fam.endswith("_causal")
         cal_L = [256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536] + ([131072] if H == 3 else [])
         rows = []
         for L in cal_L:
             n = max(1, tokens // L)
             bag = BagSpec(f"cal{L}x{n}", [L] * n, H=H, d=d, seed=1234 + L)
             dev = device_inputs_fast(bag)
-            r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+            r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev, causal=causal)
             rows.append({"L": L, "n": n, "ms": r["gpu_ms_per_step"],
-                         "tflops": 14.0 * H * d * bag.sum_l2 / (r["gpu_ms_per_step"] * 1e-3) / 1e12})
+                         "tflops": 14.0 * H * d * score_count(bag, causal) / (r["gpu_ms_per_step"] * 1e-3) / 1e12})
             log(f"[fit] {fam} {n} x L={L}: {rows[-1]['ms']:.3f} ms, {rows[-1]['tflops']:.1f} TF/s")
             del dev, r
             torch.cuda.empty_cache()
@@ -341,12 +344,12 @@ def run_fit(args):
         # equal lengths alone run a few per cent more efficiently than mixed ones and would bias the model
         # low), the benchmark bags (draw 0) and the even-numbered draws are predicted out of sample
         evals = []
-        cfgs = {"H24_d128": [1, 2, 3], "H3_d128": [4], "H12_d64": [1, 2]}[fam]
+        cfgs = {"H24_d128": [1, 2, 3], "H3_d128": [4], "H12_d64": [1, 2], "H24_d128_causal": [1, 2]}[fam]
         for ci in cfgs:
             # draw 0 is the benchmark bag; config 4 is fixed, its further "draws" are random bags of
             # power-of-two lengths (8192 .. 131072) filling the same 196608 tokens
             n_draws = args.fit_draws if ci != 4 else args.fit_draws - 1
-            if fam == "H12_d64":
+            if fam in ("H12_d64", "H24_d128_causal"):
                 n_draws = max(2, args.fit_draws // 2)
             for so in range(n_draws):
                 if ci == 4 and so > 0:
@@ -362,7 +365,7 @@ def run_fit(args):
                     if (bag.H, bag.d) != (H, d):       # the configuration's lengths at this family's shape
                         bag = BagSpec(f"{bag.name}_H{H}_d{d}", bag.seq_lens, H=H, d=d, seed=bag.seed)
                 dev = device_inputs_fast(bag)
-                r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+                r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev, causal=causal)
                 evals.append({"config": ci, "seed_offset": so, "n_seq": len(bag.seq_lens), "T": bag.total_tokens,
                               "sum_l2": bag.sum_l2, "ms": r["gpu_ms_per_step"], "role": "calibration" if so % 2 else "evaluation"})
                 log(f"[fit] {fam} cfg{ci}/{so}: measured {r['gpu_ms_per_step']:.3f} ms")
