@@ -421,3 +421,16 @@ def test_random_bags_both_masks():
             lens[int(rng.integers(0, n_seq))] = 0
         bag = BagSpec(f"random{i}", lens, H=int(rng.choice([1, 2, 5])), d=int(rng.choice([64, 128])), seed=9100 + i)
         _full_compare(bag, strict_fwd=False, causal=bool(i % 2))
+
+
+@pytest.mark.timeout(400)
+def test_quarter_million_token_sequence_sampled():
+    """Twice the longest benchmark sequence (262144 tokens, 2048 query tiles per head): sampled query rows
+    against the oracle, invariants on the GPU outputs, under both masks."""
+    bag = BagSpec("quarter_million", [262144, 77], H=2, d=128, seed=6161)
+    for causal in (False, True):
+        run = GpuRun(bag, causal=causal)
+        _sampled_compare(run, 0, 1, n_rows=24, causal=causal)
+        _sampled_compare(run, 1, 0, n_rows=8, n_cols=8, causal=causal)
+        _invariants(run, 0, 0)
+        del run
