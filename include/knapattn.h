@@ -58,12 +58,17 @@ extern "C" {
 /* out = softmax(scale * q k^T) v per (sequence, head); also writes lse.
  *
  * Concurrency.  The kernel draws its work items from counters that live in the
- * library's device image: 256 sets, handed out in rotation, each cleared on
- * `stream` right before the kernel that uses it.  Calls from several threads
- * and on several streams may overlap freely as long as no more than 256
- * forward launches are in flight on a device at the same time.  The first call
- * on a device (it looks up device properties) must not be made under stream
- * capture; later calls may be captured. */
+ * library's device image: 256 sets, each cleared on `stream` right before the
+ * kernel that uses it.  Eager launches take sets 0..127 in rotation: calls from
+ * several threads and on several streams may overlap freely as long as no more
+ * than 128 eager forward launches are in flight on a device at the same time.
+ * A launch recorded under stream capture takes one of sets 128..255 and keeps
+ * it for every replay of its graph, so replays never share a set with eager
+ * launches; two captured launches share a set only once more than 128 forward
+ * launches have been captured in the process, and graphs that hold such a pair
+ * must then not be replayed at the same time.  The first call on a device (it
+ * looks up device properties, once, under a lock) must not be made under
+ * stream capture; later calls may be captured. */
 int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
                          const int32_t* cu_seqlens, int n_seq,
                          int H, int d, float scale,
@@ -165,17 +170,6 @@ const char* knap_strerror(int code);
 
 /* The hipError_t (as int) of the most recent failed launch on this thread, 0 if none. */
 int knap_last_hip_error(void);
-
-/* Benchmark hook.  While both are non-NULL, every backward call made by this
- * thread records `start` right before and `stop` right after its dK/dV kernel
- * (the longest kernel of the path) on the call's stream; the dQ kernel, which
- * runs before it, stays outside the pair.  hipEvent_t passed as void*, owned
- * by the caller.  Pass NULLs to switch it off.  Not for use under graph capture. */
-void knap_bwd_profile_events(void* start, void* stop);
-
-/* Number of persistent workgroups the forward / backward kernels are launched
- * with on the current device (for benchmarks and tests; <= 0 on error). */
-int knap_launch_workgroups(int which /* 0 = forward, 1 = backward dK/dV, 2 = backward dQ */);
 
 /* ------------------------------------------------------------------------
  * Host-side workload model and balancer (pure C, host pointers, no GPU).

@@ -1,4 +1,5 @@
-"""ctypes binding of libknapattn.so: the same names as include/knapattn.h.
+"""ctypes binding of libknapattn.so: the same names as include/knapattn.h (and the benchmark hooks of
+include/knapattn_bench.h).
 
 Argument marshalling only.  Every step of the attention path runs in the HIP
 kernels of the shared library; PyTorch supplies device memory and the stream.
@@ -11,8 +12,7 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# KNAPATTN_LIB selects another build of the same library (e.g. a tuning variant)
-LIB_PATH = os.environ.get("KNAPATTN_LIB") or os.path.join(_HERE, "libknapattn.so")
+LIB_PATH = os.path.join(_HERE, "libknapattn.so")
 
 KNAP_OK = 0
 KNAP_ERR_INVALID_ARG = -1

@@ -1,11 +1,13 @@
 // C-ABI entry points of libknapattn: argument checks, workspace carving and
 // launches.  Nothing here allocates, frees or synchronises.
 #include "knapattn.h"
+#include "knapattn_bench.h"
 #include "knap_kernels.h"
 
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 
 namespace {
 
@@ -21,31 +23,40 @@ struct DeviceInfo {
   unsigned* fwd_queue = nullptr;   // this device's copy of the forward work-queue counters
 };
 
-std::atomic<unsigned> g_fwd_launches{0};   // picks the counter set of a forward launch
+// Counter sets of the forward's work queue: the lower half is handed out in rotation to eager launches,
+// the upper half to launches recorded under stream capture.  A captured launch keeps its set for every
+// replay of its graph, so it must never be one that eager launches rotate through.
+std::atomic<unsigned> g_fwd_launches{0};
+std::atomic<unsigned> g_fwd_captured{0};
 
-// per-device launch geometry, filled on first use (occupancy queries do not allocate)
-DeviceInfo* device_info() {
-  static DeviceInfo info[64];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return nullptr; }
-  DeviceInfo& di = info[dev];
-  if (di.cus == 0) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
-      (void)hipGetLastError();
-      return nullptr;
-    }
-    di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
-    di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
-    di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64);
-    di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
-    di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
-    di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
-    di.fwd_queue = knap::fwd_queue_base();
-    if (!di.fwd_queue) return nullptr;
-    di.cus = cus;
+constexpr int kMaxDevices = 64;
+
+void fill_device_info(DeviceInfo& di, int dev) {
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    return;
   }
-  return &di;
+  di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
+  di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
+  di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64);
+  di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
+  di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
+  di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
+  di.fwd_queue = knap::fwd_queue_base();
+  if (!di.fwd_queue) return;
+  di.cus = cus;     // last: marks the entry as complete
+}
+
+// per-device launch geometry and device-image addresses, looked up once per device with that
+// device current (occupancy and symbol queries do not allocate); nullptr if the lookup failed
+DeviceInfo* device_info() {
+  static DeviceInfo info[kMaxDevices];
+  static std::once_flag once[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  std::call_once(once[dev], fill_device_info, std::ref(info[dev]), dev);
+  return info[dev].cus > 0 ? &info[dev] : nullptr;
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -73,7 +84,15 @@ int fwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
   DeviceInfo* di = device_info();
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
   const int grid = di->cus * di->fwd_wg[d == 128];
-  unsigned* counters = di->fwd_queue + 8u * (g_fwd_launches.fetch_add(1u) % (unsigned)knap::fwd_queue_slots());
+  const unsigned half = (unsigned)knap::fwd_queue_slots() / 2u;
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    capture = hipStreamCaptureStatusNone;
+  }
+  const unsigned slot = capture == hipStreamCaptureStatusNone ? g_fwd_launches.fetch_add(1u) % half
+                                                              : half + g_fwd_captured.fetch_add(1u) % half;
+  unsigned* counters = di->fwd_queue + 8u * slot;
   const hipError_t e = knap::launch_fwd(q, k, v, cu_seqlens, n_seq, H, d, scale, causal, out, lse, counters,
                                         grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }

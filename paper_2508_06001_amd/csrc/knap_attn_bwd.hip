@@ -460,10 +460,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     // One tile: 64 keys as two halves of 32, one after the other (the register file is full with
     // the q and dO fragments and the dQ accumulator; the second wave of the SIMD fills the gaps).
     // Within a half the LDS reads are streamed a few MFMAs ahead of their use.
-    // DIAG: the tile crosses the causal diagonal; keys after this lane's query get dS = 0, and a wave
+    // MODE 2: the tile crosses the causal diagonal; keys after this lane's query get dS = 0, and a wave
     // whose 32 queries all precede the tile's first key has nothing to do in it.
-    auto process_tile = [&](auto diag_tag, int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
-      constexpr bool DIAG = decltype(diag_tag)::value;
+    // MODE 1: the ragged last tile; keys past the end of the sequence get dS = 0.  Their K and V rows
+    // arrive as zeros, so their score is 0 and P = exp2(-LSE2), which overflows for a query whose
+    // scores are all far below zero: the product with the zero K row must never be formed.
+    auto process_tile = [&](auto mode_tag, int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
+      constexpr int MODE = decltype(mode_tag)::value;
+      constexpr bool DIAG = MODE == 2;
       load_tile(t + 1, nK, nV);
       if (!(DIAG && t * C::BN > q0 + 32 * wave_u + 31)) {
 #pragma unroll
@@ -483,11 +487,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2); element e of chunk ck is key
         // 32 half + 16 ck + 8 (e / 4) + 4 hh + e % 4
         float ds[16];
-        const int last_seen = q_row - t * C::BN - 32 * half - 4 * hh;   // counted from this half's first key
+        // counted from this half's first key: the last key the lane's query sees (MODE 2), the first
+        // key past the end of the sequence (MODE 1)
+        const int last_seen = q_row - t * C::BN - 32 * half - 4 * hh;
+        const int first_past = L - t * C::BN - 32 * half - 4 * hh;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float x = fast_exp2(__builtin_fmaf(s[r], c, -lse2)) * (dp[r] - dl);
-          ds[r] = (DIAG && 8 * (r >> 2) + (r & 3) > last_seen) ? 0.f : x;
+          ds[r] = (DIAG && 8 * (r >> 2) + (r & 3) > last_seen) || (MODE == 1 && 8 * (r >> 2) + (r & 3) >= first_past)
+                      ? 0.f : x;
         }
         const bf16x8 d0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
         const bf16x8 d1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
@@ -510,21 +518,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     wait_async_loads();
     if (tid == 0 && sub == 0) next_ticket = atomicAdd(queue.ctr, 1u);
     __syncthreads();
+    constexpr std::integral_constant<int, 0> plain{};
+    constexpr std::integral_constant<int, 1> ragged_end{};
+    constexpr std::integral_constant<int, 2> diagonal{};
     if constexpr (!CAUSAL) {
-      for (int t = 0; t < n_tiles; t += 2) {
-        process_tile(std::false_type{}, t, sK0, sV0, sK1, sV1);
-        if (t + 1 < n_tiles) process_tile(std::false_type{}, t + 1, sK1, sV1, sK0, sV0);
+      const bool ragged = (L % C::BN) != 0;
+      const int n_full = ragged ? n_tiles - 1 : n_tiles;
+      for (int t = 0; t < n_full; t += 2) {
+        process_tile(plain, t, sK0, sV0, sK1, sV1);
+        if (t + 1 < n_full) process_tile(plain, t + 1, sK1, sV1, sK0, sV0);
+      }
+      if (ragged) {
+        if ((n_tiles - 1) & 1) process_tile(ragged_end, n_tiles - 1, sK1, sV1, sK0, sV0);
+        else process_tile(ragged_end, n_tiles - 1, sK0, sV0, sK1, sV1);
       }
     } else {
       // tiles 0 .. 2 q_tile - 1 lie below the diagonal (an even count: the pair loop ends on buffer 0);
       // tiles 2 q_tile and, if the sequence reaches it, 2 q_tile + 1 cross it
       const int n_below = 2 * q_tile;
       for (int t = 0; t < n_below; t += 2) {
-        process_tile(std::false_type{}, t, sK0, sV0, sK1, sV1);
-        process_tile(std::false_type{}, t + 1, sK1, sV1, sK0, sV0);
+        process_tile(plain, t, sK0, sV0, sK1, sV1);
+        process_tile(plain, t + 1, sK1, sV1, sK0, sV0);
       }
-      process_tile(std::true_type{}, n_below, sK0, sV0, sK1, sV1);
-      if (n_below + 1 < n_tiles) process_tile(std::true_type{}, n_below + 1, sK1, sV1, sK0, sV0);
+      process_tile(diagonal, n_below, sK0, sV0, sK1, sV1);
+      if (n_below + 1 < n_tiles) process_tile(diagonal, n_below + 1, sK1, sV1, sK0, sV0);
     }
 
     if (q_valid) {

@@ -168,11 +168,7 @@ __device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
 // group hints inside one fenced region ask for instruction classes in the given order,
 // which is how MFMAs get interleaved with the LDS reads and arithmetic of another stage.
 #define KNAP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#if defined(KNAP_NO_SCHED_GROUPS)
-#define KNAP_SGB(mask, n) ((void)0)
-#else
 #define KNAP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#endif
 // Interleave n_mfma MFMAs with the LDS reads that feed them (reads_per_mfma each), keeping the
 // reads `ahead` MFMAs in front of their use so that no MFMA waits out a full LDS latency.
 #define KNAP_STREAM_READS(n_mfma, reads_per_mfma, ahead)                          \

@@ -3,17 +3,17 @@ mixed_res, joint on 32 GPUs) with and without the greedy balancer, computed by t
 (knap_flux_workload, knap_parse_topology, knap_greedy_assign_weights, knap_wir; gamma = 0.49,
 d_model = 3072 as in the table's caption) and printed beside the values the paper prints.
 
-    python -m paper_2508_06001_amd.table1_wir [--seeds N]
+    python -m paper_2508_06001_amd.table1_wir [--seeds N] [--paper-table FILE]
 
 Sequence lengths follow the paper's data codes: (R/16)^2 visual tokens per frame, F frames (F / 3.4 for
 clips), text ~ U{0..392}, one aspect multiplier U[0.96, 1.04] per batch.  The "mean" column uses 196 text
 tokens and no jitter; the "random" column is the median over N seeded streams.  The paper drew its own
-random streams, so single cells differ; its values come from tests/golden/table1_wir.txt.
+random streams, so single cells differ.  --paper-table names a text file of lines
+"workload topology value" (the cells the paper prints); without it the "paper" column stays empty.
 """
 from __future__ import annotations
 
 import argparse
-import os
 
 import numpy as np
 
@@ -21,7 +21,6 @@ import paper_2508_06001_amd as K
 from knap_inputs import table1_streams
 
 D_MODEL, GAMMA = 3072, 0.49
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def wir(workload: str, topo: str, seed=None) -> float:
@@ -35,23 +34,24 @@ def wir(workload: str, topo: str, seed=None) -> float:
     return K.knap_wir(load, bags)
 
 
-def printed_cells():
+def printed_cells(path):
     cells = {}
-    path = os.path.join(ROOT, "tests", "golden", "table1_wir.txt")
-    if os.path.exists(path):
-        for line in open(path):
-            line = line.strip()
-            if line and not line.startswith("#"):
-                w, t, v = line.split()
-                cells[w, t] = float(v)
+    if path:
+        with open(path) as f:
+            for line in f:
+                line = line.strip()
+                if line and not line.startswith("#"):
+                    w, t, v = line.split()
+                    cells[w, t] = float(v)
     return cells
 
 
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--seeds", type=int, default=5)
+    ap.add_argument("--paper-table", default=None, help="text file with the cells the paper prints")
     args = ap.parse_args()
-    paper = printed_cells()
+    paper = printed_cells(args.paper_table)
     print("%-10s %-6s %8s %8s %10s" % ("workload", "bags", "paper", "mean", "random"))
     for workload in ("low_res", "mixed_res", "joint"):
         for topo in ("none", "g1n32", "g2n16", "g4n8", "g8n4"):

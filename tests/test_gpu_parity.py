@@ -2,7 +2,19 @@
 
 Bars (from the benchmark definition): forward max |out - ref| <= 1e-2; dq, dk, dv
 relative Frobenius error <= 3e-2 over the bag; diagnostics: lse max error <= 1e-3.
-All calls go through the C ABI of libknapattn.so.
+All calls go through the C ABI of libknapattn.so.  Every run (gpu_util.GpuRun) also
+asserts that all of out, lse, dq, dk, dv is finite and that the NaN guard rows around
+them are untouched, whatever a test then samples.
+
+Where the plain bars cannot hold, the relaxed ones are asked for explicitly:
+* forward, `strict_fwd=False`: max(1e-2, 2^-8 |ref|).  A stored bf16 output is half an ulp
+  (2^-9 |ref|... 2^-8 |ref|) away from the exact one, which passes 1e-2 once |ref| >= 4: near one-hot
+  rows of the peaky bags and rows that see one or two keys (1-2-token sequences, the first rows
+  of a causal sequence) return single v entries of that size.
+* lse, `lse_tol=LSE_TOL_FEW_KEYS`: the forward sums the bf16-rounded probabilities, each up to
+  2^-9 off; over many keys of similar weight that averages out (<= 5e-4 measured on the benchmark
+  bags), but a row dominated by one or two keys (peaky bags, very short or causal rows) keeps up to
+  2^-9 = 2e-3 of relative error in its sum.
 """
 import numpy as np
 import pytest
@@ -15,15 +27,16 @@ from gpu_util import GpuRun, rel_fro, say, to_f64
 pytestmark = pytest.mark.gpu
 
 FWD_TOL = 1e-2
-LSE_TOL = 3e-3      # diagnostic: the row sum is taken over bf16-rounded probabilities (<= 2^-9 relative)
+LSE_TOL = 1e-3
+LSE_TOL_FEW_KEYS = 3e-3
 BWD_TOL = 3e-2
 
 
-def _full_compare(bag: BagSpec, heads=None, strict_fwd=True, causal=False):
+def _full_compare(bag: BagSpec, heads=None, strict_fwd=True, causal=False, lse_tol=LSE_TOL, tensors=None):
     """strict_fwd: the benchmark bar max |err| <= 1e-2.  The edge-case bags hold sequences of one or
     two tokens whose outputs are as large as single v entries (|out| up to ~4); there half a bf16 ulp
     of the stored output (2^-8 |ref|) alone can pass 1e-2, so the bar is max(1e-2, 2^-8 |ref|)."""
-    run = GpuRun(bag, causal=causal)
+    run = GpuRun(bag, causal=causal, tensors=tensors)
     heads = list(range(bag.H)) if heads is None else heads
     cu = [int(c) for c in run.cu]
     worst_fwd = worst_lse = 0.0
@@ -51,7 +64,7 @@ def _full_compare(bag: BagSpec, heads=None, strict_fwd=True, causal=False):
     say(f"[parity] {bag.name}{' causal' if causal else ''}: fwd max|err|={worst_fwd:.3e} lse={worst_lse:.3e} "
         f"dq={errs['dq']:.3e} dk={errs['dk']:.3e} dv={errs['dv']:.3e}")
     assert worst_fwd <= FWD_TOL
-    assert worst_lse <= LSE_TOL
+    assert worst_lse <= lse_tol
     for n in errs:
         assert errs[n] <= BWD_TOL, (n, errs[n])
     return run
@@ -66,7 +79,7 @@ def test_ragged_lengths_span_tiles_and_tails(d):
     # lengths around every tile boundary in use (32, 64, 128), zero-length and single-token sequences
     lens = [1, 2, 31, 0, 33, 63, 64, 65, 127, 128, 129, 0, 191, 257, 300, 513, 1]
     bag = BagSpec("ragged", lens, H=3, d=d, seed=777 + d)
-    run = _full_compare(bag, strict_fwd=False)
+    run = _full_compare(bag, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
     # rows of zero-length sequences do not exist; every row < T was written (no NaN canary left)
     assert np.all(np.isfinite(to_f64(run.out_bits)))
     assert np.all(np.isfinite(run.lse))
@@ -81,7 +94,7 @@ def test_many_short_sequences():
     rng = np.random.default_rng(99)
     lens = [int(x) for x in rng.integers(1, 90, size=300)]
     bag = BagSpec("many_short", lens, H=2, d=64, seed=4343)
-    _full_compare(bag, strict_fwd=False)
+    _full_compare(bag, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
 
 
 def test_maximum_number_of_sequences():
@@ -90,12 +103,12 @@ def test_maximum_number_of_sequences():
     rng = np.random.default_rng(2048)
     lens = [int(x) for x in rng.integers(0, 48, size=K.KNAP_MAX_SEQS)]
     lens[17] = 700                                   # one sequence that spans several tiles
-    _full_compare(BagSpec("max_seqs", lens, H=2, d=128, seed=4545), strict_fwd=False)
+    _full_compare(BagSpec("max_seqs", lens, H=2, d=128, seed=4545), strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
 
 
 def test_peaky_softmax_with_outlier_keys():
     bag = BagSpec("peaky", [700, 333], H=2, d=128, seed=4444, k_outlier_prob=0.01, k_outlier_scale=8.0)
-    _full_compare(bag)
+    _full_compare(bag, lse_tol=LSE_TOL_FEW_KEYS)
 
 
 def test_mixed_res_image_bag_sampled_heads():
@@ -214,7 +227,7 @@ def test_hip_graph_replays_match_eager():
 # at any size and are checked on the GPU outputs alone.
 # ---------------------------------------------------------------------------
 
-def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0, causal=False):
+def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0, causal=False, strict_fwd=True, lse_tol=LSE_TOL):
     bag = run.bag
     cu = [int(c) for c in run.cu]
     sl = slice(cu[s], cu[s + 1])
@@ -224,12 +237,13 @@ def _sampled_compare(run, s, h, n_rows=48, n_cols=0, seed=0, causal=False):
     rows = np.unique(np.concatenate([[0, L - 1, L // 2], rng.integers(0, L, size=n_rows)]))
     O, LSE, dQ = A.attn_query_rows(Q, K_, V, dO, rows, bag.scale, causal)
     err_out = np.abs(run.host("out", sl, h)[rows] - O)
-    err_out = np.where(err_out <= 2.0 ** -8 * np.abs(O), 0.0, err_out)     # bf16 resolution of the stored output
+    if not strict_fwd:
+        err_out = np.where(err_out <= 2.0 ** -8 * np.abs(O), 0.0, err_out)     # bf16 resolution of the stored output
     e_out = float(np.max(err_out))
     e_lse = float(np.max(np.abs(run.lse[h, sl][rows] - LSE)))
     e_dq = rel_fro(run.host("dq", sl, h)[rows], dQ)
     msg = f"[parity] {bag.name} seq {s} (L={L}) head {h}: out={e_out:.3e} lse={e_lse:.3e} dq={e_dq:.3e}"
-    assert e_out <= FWD_TOL and e_lse <= LSE_TOL and e_dq <= BWD_TOL, msg
+    assert e_out <= FWD_TOL and e_lse <= lse_tol and e_dq <= BWD_TOL, msg
     if n_cols:
         cols = np.unique(np.concatenate([[0, L - 1], rng.integers(0, L, size=n_cols)]))
         dKc, dVc = A.attn_key_cols(Q, K_, V, dO, cols, bag.scale, causal)
@@ -273,13 +287,18 @@ def test_image_video_bag_sampled():
 
 
 @pytest.mark.timeout(400)
-@pytest.mark.parametrize("long_position", ["first", "last"])
+@pytest.mark.parametrize("long_position", ["first", "middle", "last"])
 def test_skewed_bag_sampled(long_position):
-    """Benchmark config 3 at full size: one 65536-token sequence among 200 short ones, peaky softmax."""
+    """Benchmark config 3 at full size: one 65536-token sequence among 200 short ones, peaky softmax
+    (1 % of the k entries scaled by 8: the relaxed forward and lse bars of the module docstring apply).
+    The long sequence sits first, in the middle or last in the bag; its dk and dv are compared on sampled
+    key rows in every position."""
     bag = config_bag(3, long_position=long_position)
     run = GpuRun(bag)
     s_long = bag.seq_lens.index(65536)
-    _sampled_compare(run, s_long, 7, n_rows=40, n_cols=24 if long_position == "first" else 0)
+    assert s_long == {"first": 0, "middle": 100, "last": 200}[long_position]
+    _sampled_compare(run, s_long, {"first": 7, "middle": 0, "last": 23}[long_position], n_rows=40,
+                     n_cols=24 if long_position == "first" else 16, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
     _invariants(run, s_long, 19)
     # a few short sequences, full oracle per (sequence, head)
     cu = [int(c) for c in run.cu]
@@ -294,7 +313,7 @@ def test_skewed_bag_sampled(long_position):
             # output already exceeds 1e-2, so the bar there is the output type's resolution 2^-8 |ref|
             err = np.abs(run.host("out", sl, h) - O)
             assert np.all(err <= np.maximum(FWD_TOL, 2.0 ** -8 * np.abs(O))), (s, h, float(err.max()))
-            assert np.max(np.abs(run.lse[h, sl] - LSE)) <= LSE_TOL
+            assert np.max(np.abs(run.lse[h, sl] - LSE)) <= LSE_TOL_FEW_KEYS
             for name, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
                 assert rel_fro(run.host(name, sl, h), ref) <= BWD_TOL, (name, s, h)
 
@@ -304,11 +323,30 @@ def test_post_ulysses_share_sampled():
     """Benchmark config 4 at full size: H = 3 local heads, sequences up to 131072 tokens."""
     bag = config_bag(4)
     run = GpuRun(bag)
-    _sampled_compare(run, 0, 1, n_rows=40)                  # 131072 tokens: query rows
+    # 131072 tokens: query rows here; one exact pass for its key rows costs the oracle 4 L^2 d = 9e12
+    # float64 operations, so its dk and dv are compared element by element through the properties of
+    # tests/test_gpu_closed_forms.py instead (periodic sequence, zero keys), at this very shape
+    _sampled_compare(run, 0, 1, n_rows=40)
     _sampled_compare(run, 1, 2, n_rows=40, n_cols=32)       # 32768 tokens: query rows and key rows
     _sampled_compare(run, 3, 0, n_rows=40, n_cols=32)       # 8192 tokens
     for s in range(len(bag.seq_lens)):
         _invariants(run, s, s % 3)
+
+
+def test_all_scores_far_below_zero_with_ragged_tails():
+    """Every score of a query is about -135, so exp(-LSE) overflows float32, and no length is a multiple of a
+    key tile: the zero rows a ragged last tile is padded with must not reach dq (0 x inf), nor anything
+    else.  Checked against the oracle like any other bag."""
+    from knap_inputs import bf16_bits_to_f32, f32_to_bf16_bits
+    for d in (128, 64):
+        bag = BagSpec(f"far_below_zero_d{d}", [100, 65, 200, 1, 333], H=2, d=d, seed=4646 + d)
+        t = make_qkv_dout(bag)
+        noise = {n: bf16_bits_to_f32(t[n]) for n in ("q", "k")}
+        alpha = 135.0 / (bag.scale * d)                      # q . k = -alpha d, times scale = -135
+        t["q"] = f32_to_bf16_bits(1.0 + 0.05 * noise["q"])
+        t["k"] = f32_to_bf16_bits(-alpha + 0.05 * noise["k"])
+        run = _full_compare(bag, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS, tensors=t)
+        assert float(np.max(run.lse)) < -100.0
 
 
 # ---------------------------------------------------------------------------
@@ -318,7 +356,7 @@ def test_post_ulysses_share_sampled():
 # ---------------------------------------------------------------------------
 
 def test_causal_tiny_bag_full_oracle():
-    _full_compare(config_bag(0), strict_fwd=False, causal=True)
+    _full_compare(config_bag(0), strict_fwd=False, causal=True, lse_tol=LSE_TOL_FEW_KEYS)
 
 
 @pytest.mark.parametrize("d", [64, 128])
@@ -326,18 +364,21 @@ def test_causal_ragged_lengths_around_every_tile_boundary(d):
     # query tiles are 128 rows, key tiles 64 / 128: lengths on both sides of each multiple, pairs of
     # tiles with and without a middle tile (odd and even tile counts), zero-length and 1-token sequences
     lens = [1, 2, 63, 64, 65, 0, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 385, 513, 640, 1]
-    run = _full_compare(BagSpec("causal_ragged", lens, H=3, d=d, seed=1777 + d), strict_fwd=False, causal=True)
+    run = _full_compare(BagSpec("causal_ragged", lens, H=3, d=d, seed=1777 + d), strict_fwd=False, causal=True,
+                        lse_tol=LSE_TOL_FEW_KEYS)
     assert np.all(np.isfinite(to_f64(run.out_bits))) and np.all(np.isfinite(run.lse))
 
 
 def test_causal_long_sequences_many_tile_pairs():
-    _full_compare(BagSpec("causal_long", [2500, 1111, 77], H=2, d=128, seed=5252), strict_fwd=False, causal=True)
+    _full_compare(BagSpec("causal_long", [2500, 1111, 77], H=2, d=128, seed=5252), strict_fwd=False, causal=True,
+                  lse_tol=LSE_TOL_FEW_KEYS)
 
 
 def test_causal_many_short_sequences():
     rng = np.random.default_rng(199)
     lens = [int(x) for x in rng.integers(1, 200, size=150)]
-    _full_compare(BagSpec("causal_short", lens, H=2, d=64, seed=5353), strict_fwd=False, causal=True)
+    _full_compare(BagSpec("causal_short", lens, H=2, d=64, seed=5353), strict_fwd=False, causal=True,
+                  lse_tol=LSE_TOL_FEW_KEYS)
 
 
 def test_causal_first_row_returns_its_own_value_and_differs_from_full():
@@ -363,9 +404,9 @@ def test_causal_mixed_res_image_bag_sampled():
     run = GpuRun(bag, causal=True)
     longest = int(np.argmax(bag.seq_lens))
     shortest = int(np.argmin(bag.seq_lens))
-    _sampled_compare(run, longest, 3, n_rows=48, n_cols=48, causal=True)
-    _sampled_compare(run, shortest, 20, n_rows=48, n_cols=48, causal=True)
-    _sampled_compare(run, 1, 12, n_rows=32, n_cols=16, causal=True)
+    _sampled_compare(run, longest, 3, n_rows=48, n_cols=48, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, shortest, 20, n_rows=48, n_cols=48, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, 1, 12, n_rows=32, n_cols=16, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
     for s in (longest, shortest):
         _invariants(run, s, 7)          # rows of P still sum to one; <Q,dQ> = <K,dK>
 
@@ -375,9 +416,9 @@ def test_causal_post_ulysses_share_sampled():
     """Benchmark config 4 at full size under the causal mask (131072-token sequence, 512 tile pairs)."""
     bag = config_bag(4)
     run = GpuRun(bag, causal=True)
-    _sampled_compare(run, 0, 1, n_rows=40, causal=True)
-    _sampled_compare(run, 1, 2, n_rows=40, n_cols=32, causal=True)
-    _sampled_compare(run, 3, 0, n_rows=40, n_cols=32, causal=True)
+    _sampled_compare(run, 0, 1, n_rows=40, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, 1, 2, n_rows=40, n_cols=32, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, 3, 0, n_rows=40, n_cols=32, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
     for s in range(len(bag.seq_lens)):
         _invariants(run, s, s % 3)
 
@@ -420,7 +461,7 @@ def test_random_bags_both_masks():
         if i % 3 == 0:
             lens[int(rng.integers(0, n_seq))] = 0
         bag = BagSpec(f"random{i}", lens, H=int(rng.choice([1, 2, 5])), d=int(rng.choice([64, 128])), seed=9100 + i)
-        _full_compare(bag, strict_fwd=False, causal=bool(i % 2))
+        _full_compare(bag, strict_fwd=False, causal=bool(i % 2), lse_tol=LSE_TOL_FEW_KEYS)
 
 
 @pytest.mark.timeout(400)
@@ -430,7 +471,9 @@ def test_quarter_million_token_sequence_sampled():
     bag = BagSpec("quarter_million", [262144, 77], H=2, d=128, seed=6161)
     for causal in (False, True):
         run = GpuRun(bag, causal=causal)
-        _sampled_compare(run, 0, 1, n_rows=24, causal=causal)
-        _sampled_compare(run, 1, 0, n_rows=8, n_cols=8, causal=causal)
+        _sampled_compare(run, 0, 1, n_rows=24, causal=causal, strict_fwd=not causal,
+                         lse_tol=LSE_TOL_FEW_KEYS if causal else LSE_TOL)
+        _sampled_compare(run, 1, 0, n_rows=8, n_cols=8, causal=causal, strict_fwd=not causal,
+                         lse_tol=LSE_TOL_FEW_KEYS if causal else LSE_TOL)
         _invariants(run, 0, 0)
         del run

@@ -15,8 +15,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    with open(os.path.join(ROOT, "include", "knapattn.h")) as f:
-        text = f.read()
+    text = ""
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        assert header.endswith(".h"), header
+        with open(os.path.join(ROOT, "include", header)) as f:
+            text += f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(knap_[a-z0-9_]+)\s*\(", text))
     assert declared, "no declarations found"
@@ -149,8 +152,9 @@ def test_table1_wir_script_reproduces_the_printed_column():
     """The user-facing reproduction (C balancer on the paper's data-code streams) stays in the bands of
     the cells the paper prints (the paper drew its own random streams)."""
     from paper_2508_06001_amd import table1_wir as T
-    printed = T.printed_cells()
+    printed = T.printed_cells(os.path.join(ROOT, "tests", "golden", "table1_wir.txt"))
     assert len(printed) == 15
+    assert T.printed_cells(None) == {}
     for (workload, topo), val in printed.items():
         got = float(np.median([T.wir(workload, topo, s) for s in range(5)]))
         if topo == "none":
