@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the packed variable-length attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-cpu-baseline] [--no-model]
     python bench.py --fit            # cost-model calibration + per-bag residuals (long; writes a report)
 
 A step is one pass of the whole hot path over one bag: the forward call and the
-backward call through the C ABI, inputs resident in HBM.  Default workload:
-the ~32k-token mixed-resolution image bag (benchmark config 1).  One JSON line
-is printed at the end.
+backward call through the C ABI, inputs resident in HBM.  Default: the four
+performance bags (benchmark configs 1-4) are timed K steps each in one run; the
+headline figures are those of the largest, config 3 (one 65536-token sequence
+among 200 short ones, 185 TFLOP per step), the other three and the minimum ride
+along in `per_config`; `model_rel_resid` is each bag's distance from the cost
+model a sum(L^2) + b sum(L) fitted in the same run on single-length bags only.
+One JSON line is printed at the end.
 
 FLOP convention: 14 H d sum(L^2) per step (4 forward + 10 recompute backward;
 Eq. 1's 4 l^2 d per forward); tile padding is never counted.
@@ -175,10 +179,12 @@ def time_bag(bag, dev, steps: int, warmup: int, ev: HipEvents, causal: bool = Fa
     }
 
 
-def cpu_baseline(bag, bits, budget_s: float = 20.0, causal: bool = False):
-    """The fp64 oracle, as it stands, on the host cores: forward + backward of whole
-    (sequence, head) units of the same bag, added longest-first-agnostic in bag order
-    for head 0, 1, ... until about `budget_s` seconds of CPU work have been spent."""
+def cpu_baseline(bag, bits, budget_s: float = 20.0, causal: bool = False, long_unit: int = 8192, row_block: int = 1024):
+    """The fp64 oracle, as it stands, on the host cores, on a bounded sample of the same bag: (sequence,
+    head) units in bag order for head 0, 1, ... until about `budget_s` seconds of CPU work have been
+    spent.  A unit of up to `long_unit` tokens is evaluated whole, forward + backward (14 L^2 d FLOPs);
+    of a longer one (a whole 65536-token unit alone would take a minute) the oracle evaluates a block of
+    `row_block` query rows exactly: their out, lse and dq rows, four n x L x d products (8 n L d FLOPs)."""
     from knap_inputs import bf16_bits_to_f32
     from oracle import attention as A
     try:
@@ -188,7 +194,7 @@ def cpu_baseline(bag, bits, budget_s: float = 20.0, causal: bool = False):
         threads = os.cpu_count() or 1
     cu = np.concatenate([[0], np.cumsum(bag.seq_lens)]).astype(np.int64)
     done_flops = 0.0
-    units = 0
+    units = blocks = 0
     t0 = time.perf_counter()
     stop = False
     for h in range(bag.H):
@@ -198,19 +204,30 @@ def cpu_baseline(bag, bits, budget_s: float = 20.0, causal: bool = False):
                 continue
             sl = slice(int(cu[s]), int(cu[s + 1]))
             Q, K_, V, dO = (bf16_bits_to_f32(bits[n][sl, h, :]).astype(np.float64) for n in ("q", "k", "v", "dout"))
-            A.attn_fwd_dense(Q, K_, V, bag.scale, causal)
-            A.attn_bwd_dense(Q, K_, V, dO, bag.scale, causal)
-            done_flops += 14.0 * bag.d * (L * (L + 1) / 2 if causal else L * L)
-            units += 1
+            if L <= long_unit:
+                A.attn_fwd_dense(Q, K_, V, bag.scale, causal)
+                A.attn_bwd_dense(Q, K_, V, dO, bag.scale, causal)
+                done_flops += 14.0 * bag.d * (L * (L + 1) / 2 if causal else L * L)
+                units += 1
+            else:
+                r0 = (h * row_block) % (L - row_block + 1)
+                rows = np.arange(r0, r0 + row_block)
+                A.attn_query_rows(Q, K_, V, dO, rows, bag.scale, causal)
+                pairs = float(np.sum(rows + 1)) if causal else float(row_block) * L
+                done_flops += 8.0 * bag.d * pairs
+                blocks += 1
             if time.perf_counter() - t0 > budget_s:
                 stop = True
                 break
         if stop:
             break
     dt = time.perf_counter() - t0
+    what = f"{units} whole (sequence, head) units (fwd+bwd)"
+    if blocks:
+        what += f" and {blocks} blocks of {row_block} query rows (out, lse, dq) of the sequences above {long_unit} tokens"
     return {
         "value": done_flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{units} (sequence, head) units of the same bag, fwd+bwd, {dt:.1f} s of fp64 numpy",
+        "sample": f"{what} of the same bag, {dt:.1f} s of fp64 numpy",
     }
 
 
@@ -225,64 +242,140 @@ def measured_traffic(workload: str, kernel: str):
         return None
 
 
-def run_default(args):
+CAL_LENGTHS = [256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536]
+
+
+def calibrate_model(H: int, d: int, tokens: int, ev: HipEvents, steps: int = 5, warmup: int = 2):
+    """Sec. 3.1 / Fig. 2 procedure: measure bags of ONE length each (n equal sequences filling `tokens`
+    tokens, L from 256 up to the longest the shape meets), fit a, b of t = a sum(L^2) + b sum(L) on
+    them alone with the library's relative least squares.  Returns (a, b, rows)."""
     import torch
     import paper_2508_06001_amd as K
-    from knap_inputs import config_bag
+    from knap_inputs import BagSpec
+    rows = []
+    for L in CAL_LENGTHS + ([131072] if tokens >= 131072 else []):
+        n = max(1, tokens // L)
+        bag = BagSpec(f"cal{L}x{n}", [L] * n, H=H, d=d, seed=1234 + L)
+        dev = device_inputs_fast(bag)
+        r = time_bag(bag, dev, steps=steps, warmup=warmup, ev=ev)
+        rows.append({"L": L, "n": n, "ms": r["gpu_ms_per_step"]})
+        del dev, r
+        torch.cuda.empty_cache()
+    a, b, resid = K.knap_fit_cost_model([float(r["n"]) * float(r["L"]) ** 2 for r in rows],
+                                        [float(r["n"]) * float(r["L"]) for r in rows], [r["ms"] for r in rows])
+    return a, b, resid, rows
 
-    bag = config_bag(args.config)
-    log(f"[bench] config {args.config} ({bag.name}): n_seq={len(bag.seq_lens)} T={bag.total_tokens} "
+
+def measure_config(ci: int, args, ev: HipEvents, causal: bool):
+    """Times K steps of one benchmark bag; returns the figures of that bag."""
+    import torch
+    from knap_inputs import config_bag
+    bag = config_bag(ci)
+    log(f"[bench] config {ci} ({bag.name}): n_seq={len(bag.seq_lens)} T={bag.total_tokens} "
         f"H={bag.H} d={bag.d} maxL={max(bag.seq_lens)} sumL2={bag.sum_l2:.4g}")
-    if args.config <= 1:
+    if ci <= 1:
         bits, dev = device_inputs(bag)
     else:
         bits, dev = None, device_inputs_fast(bag)
     # a second input set of the same bag (other values), used in rotation, so that a small bag's
     # inputs are not simply still sitting in the cache from the previous step
     dev = [dev, device_inputs_fast(bag, seed=1)]
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    ev = HipEvents()
-    causal = bool(args.causal)
     r = time_bag(bag, dev, args.steps, args.warmup, ev, causal)
+    del dev
+    r.pop("attn")
+    torch.cuda.empty_cache()
     ms = r["gpu_ms_per_step"]
     total_flops = flops_fwd(bag, causal) + flops_bwd(bag, causal)
     value = total_flops / (ms * 1e-3) / 1e12
     bwd_main_tflops = flops_dkdv_kernel(bag, causal) / (r["bwd_main_ms"] * 1e-3) / 1e12
     fwd_tflops = flops_fwd(bag, causal) / (r["fwd_ms"] * 1e-3) / 1e12
-    log(f"[bench] ms/step={ms:.3f} (wall {r['wall_ms_per_step']:.3f}) fwd={r['fwd_ms']:.3f} ms ({fwd_tflops:.1f} TF/s) "
+    log(f"[bench] config {ci}: ms/step={ms:.3f} (wall {r['wall_ms_per_step']:.3f}) -> {value:.1f} TF/s = "
+        f"{100 * value / PEAK_BF16_TFLOPS:.1f} % of peak; fwd={r['fwd_ms']:.3f} ms ({fwd_tflops:.1f} TF/s) "
         f"bwd={r['bwd_ms']:.3f} ms, dK/dV kernel={r['bwd_main_ms']:.3f} ms ({bwd_main_tflops:.1f} TF/s), "
         f"dQ kernel (with delta)={r['bwd_ms'] - r['bwd_main_ms']:.3f} ms")
+    return {"bag": bag, "bits": bits, "r": r, "ms": ms, "flops": total_flops, "value": value,
+            "bwd_main_tflops": bwd_main_tflops, "fwd_tflops": fwd_tflops}
+
+
+def config_summary(ci: int, m, causal: bool):
+    bag, r = m["bag"], m["r"]
+    return {"workload": f"configs[{ci}] {bag.name}" + (" (causal mask)" if causal else ""),
+            "n_seq": len(bag.seq_lens), "total_tokens": bag.total_tokens, "H": bag.H, "d": bag.d,
+            "max_len": max(bag.seq_lens), "flops_per_step": m["flops"],
+            "ms_per_step": round(m["ms"], 4), "value": round(m["value"], 3),
+            "pct_of_bf16_mfma_peak": round(100.0 * m["value"] / PEAK_BF16_TFLOPS, 2),
+            "fwd_ms": round(r["fwd_ms"], 4), "bwd_ms": round(r["bwd_ms"], 4), "fwd_tflops": round(m["fwd_tflops"], 2),
+            "dkdv_kernel_ms": round(r["bwd_main_ms"], 4), "dkdv_kernel_tflops": round(m["bwd_main_tflops"], 2)}
+
+
+def run_default(args):
+    """Default: the four performance bags (configs 1-4), K timed steps each, in one run.  The headline
+    (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the largest of them, config 3 (185 TFLOP per
+    step); the others and the minimum over all four ride along in `per_config`.  --config N times that
+    bag alone and makes it the headline."""
+    configs = [1, 2, 3, 4] if args.config is None else [args.config]
+    head = 3 if 3 in configs else configs[-1]
+    ev = HipEvents()
+    causal = bool(args.causal)
+    if args.copy_calibration:
+        import torch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    meas = {ci: measure_config(ci, args, ev, causal) for ci in configs}
+    m = meas[head]
+    bag, r = m["bag"], m["r"]
     out = {
         "metric": "varlen attention fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak",
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(m["value"], 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(m["ms"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {bag.name}" + (" (causal mask)" if causal else ""),
+        "config": {"workload": f"configs[{head}] {bag.name}" + (" (causal mask)" if causal else ""),
                    "n_seq": len(bag.seq_lens),
                    "total_tokens": bag.total_tokens, "H": bag.H, "d": bag.d, "max_len": max(bag.seq_lens),
-                   "seed": bag.seed, "flops_per_step": total_flops,
+                   "seed": bag.seed, "flops_per_step": m["flops"],
                    "flop_convention": "14*H*d*sum(L(L+1)/2) (4 fwd + 10 recompute bwd; masked pairs not counted)"
                    if causal else "14*H*d*sum(L^2) (4 fwd + 10 recompute bwd)"},
-        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "paper_convention_tflops": round(value * 12.0 / 14.0, 3),
+        "pct_of_bf16_mfma_peak": round(100.0 * m["value"] / PEAK_BF16_TFLOPS, 2),
+        "paper_convention_tflops": round(m["value"] * 12.0 / 14.0, 3),
         "fwd_ms": round(r["fwd_ms"], 4), "bwd_ms": round(r["bwd_ms"], 4),
-        "fwd_tflops": round(fwd_tflops, 2),
+        "fwd_tflops": round(m["fwd_tflops"], 2),
         "ms_per_step_median": round(r["step_ms_median"], 4), "ms_per_step_min": round(r["step_ms_min"], 4),
         "fwd_ms_median": round(r["fwd_ms_median"], 4), "bwd_ms_median": round(r["bwd_ms_median"], 4),
         "input_sets": 2,
-        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel", "achieved": round(bwd_main_tflops, 2),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_main_tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel", "achieved": round(m["bwd_main_tflops"], 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(m["bwd_main_tflops"] / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_ms": round(r["bwd_main_ms"], 4),
                      "flops_per_launch": flops_dkdv_kernel(bag, causal),
                      "traffic": None if causal else
-                     measured_traffic(f"configs[{args.config}]", "attn_bwd_dkdv_kernel")},
+                     measured_traffic(f"configs[{head}]", "attn_bwd_dkdv_kernel")},
+        "per_config": [config_summary(ci, meas[ci], causal) for ci in configs],
+        "min_pct_of_peak_over_configs": round(min(100.0 * meas[ci]["value"] / PEAK_BF16_TFLOPS for ci in configs), 2),
     }
+    if not args.no_model and not causal:
+        # cost-model check, out of sample: a, b fitted in this run on single-length bags only, then the
+        # benchmark bags timed above are predicted; |t - (a sum(L^2) + b sum(L))| / t per bag (bar: 5 %)
+        fams, resid = {}, {}
+        for ci in configs:
+            b_ = meas[ci]["bag"]
+            key = (b_.H, b_.d)
+            if key not in fams:
+                tokens = 196608 if b_.H <= 3 else 65536
+                a_, b__, cal_resid, rows = calibrate_model(b_.H, b_.d, tokens, ev)
+                fams[key] = (a_, b__, cal_resid)
+                log(f"[bench] model H={b_.H} d={b_.d}: a={a_:.4e} ms/token^2 b={b__:.4e} ms/token, "
+                    f"calibration residual <= {100 * cal_resid:.1f} % over {len(rows)} single-length bags")
+            a_, b__, _ = fams[key]
+            pred = a_ * b_.sum_l2 + b__ * b_.total_tokens
+            resid[f"configs[{ci}]"] = round(abs(meas[ci]["ms"] - pred) / meas[ci]["ms"], 4)
+            log(f"[bench] model config {ci}: measured {meas[ci]['ms']:.3f} ms, model {pred:.3f} ms, residual {100 * resid[f'configs[{ci}]']:.1f} %")
+        out["model_rel_resid"] = resid
+        out["model"] = {f"H{k[0]}_d{k[1]}": {"a_ms_per_token2": v[0], "b_ms_per_token": v[1],
+                                             "calibration_max_rel_resid": round(v[2], 4)} for k, v in fams.items()}
     if not args.no_cpu_baseline:
+        bits = m["bits"]
         if bits is None:
             from knap_inputs import make_qkv_dout
             bits = make_qkv_dout(bag)
@@ -573,7 +666,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4 (default 1)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="time one benchmark configuration 0..4 alone (default: configs 1-4, headline config 3)")
+    ap.add_argument("--no-model", action="store_true",
+                    help="skip the in-run cost-model calibration on single-length bags and the per-bag residuals")
     ap.add_argument("--causal", action="store_true",
                     help="time the causal entry points (not the headline workload) on the same bag")
     ap.add_argument("--no-cpu-baseline", action="store_true")

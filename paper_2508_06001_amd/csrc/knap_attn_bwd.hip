@@ -462,9 +462,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     // Within a half the LDS reads are streamed a few MFMAs ahead of their use.
     // MODE 2: the tile crosses the causal diagonal; keys after this lane's query get dS = 0, and a wave
     // whose 32 queries all precede the tile's first key has nothing to do in it.
-    // MODE 1: the ragged last tile; keys past the end of the sequence get dS = 0.  Their K and V rows
-    // arrive as zeros, so their score is 0 and P = exp2(-LSE2), which overflows for a query whose
-    // scores are all far below zero: the product with the zero K row must never be formed.
+    // MODE 1: the ragged last tile; the scores of keys past the end of the sequence start (and stay) at
+    // -inf, so P = 0 and dS = 0 there.  Their K and V rows arrive as zeros: left at score 0, P would be
+    // exp2(-LSE2), which overflows for a query whose scores are all far below zero, and the product of
+    // that dS with the zero K row would be NaN.
     auto process_tile = [&](auto mode_tag, int t, const __bf16* tK, const __bf16* tV, __bf16* nK, __bf16* nV) {
       constexpr int MODE = decltype(mode_tag)::value;
       constexpr bool DIAG = MODE == 2;
@@ -473,6 +474,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         f32x16 s = zero16(), dp = zero16();
+        if constexpr (MODE == 1) {
+          const int first_past = L - t * C::BN - 32 * half - 4 * hh;   // counted from this half's first key
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[r] = 8 * (r >> 2) + (r & 3) >= first_past ? -INFINITY : 0.f;
+        }
 #pragma unroll
         for (int cc = 0; cc < C::KC; ++cc) {
           s = mfma32(rows.get(tK, 32 * half, cc), qf[cc], s);
@@ -487,15 +493,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         // dS^T = P^T (dP^T - delta), P^T = exp2(c S^T - LSE2); element e of chunk ck is key
         // 32 half + 16 ck + 8 (e / 4) + 4 hh + e % 4
         float ds[16];
-        // counted from this half's first key: the last key the lane's query sees (MODE 2), the first
-        // key past the end of the sequence (MODE 1)
-        const int last_seen = q_row - t * C::BN - 32 * half - 4 * hh;
-        const int first_past = L - t * C::BN - 32 * half - 4 * hh;
+        const int last_seen = q_row - t * C::BN - 32 * half - 4 * hh;   // counted from this half's first key
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float x = fast_exp2(__builtin_fmaf(s[r], c, -lse2)) * (dp[r] - dl);
-          ds[r] = (DIAG && 8 * (r >> 2) + (r & 3) > last_seen) || (MODE == 1 && 8 * (r >> 2) + (r & 3) >= first_past)
-                      ? 0.f : x;
+          ds[r] = (DIAG && 8 * (r >> 2) + (r & 3) > last_seen) ? 0.f : x;
         }
         const bf16x8 d0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
         const bf16x8 d1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
@@ -528,9 +530,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
         process_tile(plain, t, sK0, sV0, sK1, sV1);
         if (t + 1 < n_full) process_tile(plain, t + 1, sK1, sV1, sK0, sV0);
       }
-      if (ragged) {
-        if ((n_tiles - 1) & 1) process_tile(ragged_end, n_tiles - 1, sK1, sV1, sK0, sV0);
-        else process_tile(ragged_end, n_tiles - 1, sK0, sV0, sK1, sV1);
+      if (ragged) {     // one instantiation for either buffer: the tile after the last is never loaded (empty descriptor)
+        const bool odd = (n_tiles - 1) & 1;
+        process_tile(ragged_end, n_tiles - 1, odd ? sK1 : sK0, odd ? sV1 : sV0, odd ? sK0 : sK1, odd ? sV0 : sV1);
       }
     } else {
       // tiles 0 .. 2 q_tile - 1 lie below the diagonal (an even count: the pair loop ends on buffer 0);

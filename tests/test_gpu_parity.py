@@ -334,17 +334,18 @@ def test_post_ulysses_share_sampled():
 
 
 def test_all_scores_far_below_zero_with_ragged_tails():
-    """Every score of a query is about -135, so exp(-LSE) overflows float32, and no length is a multiple of a
-    key tile: the zero rows a ragged last tile is padded with must not reach dq (0 x inf), nor anything
-    else.  Checked against the oracle like any other bag."""
+    """Every score is about -135 (coordinate 0 of every q is 32 and of every k is -135 / (32 scale); the other
+    coordinates are N(0,1) as usual), so exp(-LSE) overflows float32, and no length is a multiple of a key
+    tile: the zero rows a ragged last tile is padded with must not reach dq (0 x inf), nor anything else.
+    Checked against the oracle like any other bag."""
     from knap_inputs import bf16_bits_to_f32, f32_to_bf16_bits
     for d in (128, 64):
         bag = BagSpec(f"far_below_zero_d{d}", [100, 65, 200, 1, 333], H=2, d=d, seed=4646 + d)
         t = make_qkv_dout(bag)
-        noise = {n: bf16_bits_to_f32(t[n]) for n in ("q", "k")}
-        alpha = 135.0 / (bag.scale * d)                      # q . k = -alpha d, times scale = -135
-        t["q"] = f32_to_bf16_bits(1.0 + 0.05 * noise["q"])
-        t["k"] = f32_to_bf16_bits(-alpha + 0.05 * noise["k"])
+        q, k = bf16_bits_to_f32(t["q"]), bf16_bits_to_f32(t["k"])
+        q[:, :, 0] = 32.0
+        k[:, :, 0] = -135.0 / (32.0 * bag.scale)
+        t["q"], t["k"] = f32_to_bf16_bits(q), f32_to_bf16_bits(k)
         run = _full_compare(bag, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS, tensors=t)
         assert float(np.max(run.lse)) < -100.0
 
