@@ -24,6 +24,7 @@ extern "C" {
 #define KNAP_ERR_TOO_MANY_SEQS        -4  /* n_seq above KNAP_MAX_SEQS */
 #define KNAP_ERR_CAPACITY             -5  /* an output array of a host function is too small */
 #define KNAP_ERR_PARSE                -6  /* malformed topology string */
+#define KNAP_ERR_SCRATCH_TOO_SMALL    -7  /* the bag exceeds the library's own scratch (knap_varlen_attn_bwd_noalloc) */
 
 /* Largest number of sequences in one packed bag.  Every workgroup rebuilds the
  * tile schedule from cu_seqlens in LDS, which bounds the bag size. */
@@ -97,6 +98,31 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          void* stream);
 
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d);
+
+/* knap_varlen_attn_bwd for callers that cannot allocate a workspace: code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid
+ * hipMalloc.  Same arguments without `workspace`, same kernels, same results
+ * bit for bit.  The scratch (the per-row dot products of dout and out, one
+ * float per (row, head), plus 256 bytes of work-queue counters) is an array in
+ * the library's device image, KNAP_NOALLOC_MAX_ROWS floats + 256 bytes = 16 MiB
+ * + 256 bytes that every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing and synchronises nothing.
+ * Limit: total_tokens * H <= KNAP_NOALLOC_MAX_ROWS, else
+ * KNAP_ERR_SCRATCH_TOO_SMALL (nothing is enqueued).
+ * Every call on a GPU shares that GPU's array, which keeps the previous call's
+ * contents (each call overwrites all it reads): calls that may overlap on one
+ * GPU (different streams, or graphs replayed at the same time) race on it and
+ * must use knap_varlen_attn_bwd with a workspace each instead.  As for the
+ * forward, the first call of the library on a device must not be captured. */
+#define KNAP_NOALLOC_MAX_ROWS (4 * 1024 * 1024)
+int knap_varlen_attn_bwd_noalloc(const void* q, const void* k, const void* v,
+                                 const int32_t* cu_seqlens, int n_seq,
+                                 int H, int d, float scale,
+                                 const void* out, const float* lse,
+                                 const void* dout,
+                                 void* dq, void* dk, void* dv,
+                                 int64_t total_tokens,
+                                 void* stream);
 
 /* The same two calls under the other homogeneous mask the paper admits inside a
  * datum (Limitations paragraph: bidirectional full attention or causal

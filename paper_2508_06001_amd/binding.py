@@ -21,6 +21,8 @@ KNAP_ERR_LAUNCH_FAILED = -3
 KNAP_ERR_TOO_MANY_SEQS = -4
 KNAP_ERR_CAPACITY = -5
 KNAP_ERR_PARSE = -6
+KNAP_ERR_SCRATCH_TOO_SMALL = -7
+KNAP_NOALLOC_MAX_ROWS = 4 * 1024 * 1024
 KNAP_MAX_SEQS = 2048
 KNAP_ULYSSES_MAX_GPUS = 64
 
@@ -44,6 +46,7 @@ _SIGNATURES = {
     "knap_varlen_attn_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp]),
     "knap_varlen_attn_bwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "knap_varlen_attn_bwd_workspace_bytes": (_sz, [_i64, _i, _i, _i]),
+    "knap_varlen_attn_bwd_noalloc": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp]),
     "knap_varlen_attn_causal_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp]),
     "knap_varlen_attn_causal_bwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "knap_ulysses_pack_heads": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp]),
@@ -135,6 +138,18 @@ def knap_varlen_attn_bwd(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale:
                                   total_tokens, _ptr(workspace), workspace_bytes, _stream_handle(stream))
     if check:
         _check(rc, "knap_varlen_attn_bwd")
+    return rc
+
+
+def knap_varlen_attn_bwd_noalloc(q, k, v, cu_seqlens, n_seq: int, H: int, d: int, scale: float, out, lse, dout,
+                                 dq, dk, dv, total_tokens: int, stream=None, check: bool = True) -> int:
+    """knap_varlen_attn_bwd without a workspace argument: the scratch is an array in the library's device
+    image (total_tokens * H <= KNAP_NOALLOC_MAX_ROWS)."""
+    rc = lib.knap_varlen_attn_bwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), n_seq, H, d, scale,
+                                          _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                                          total_tokens, _stream_handle(stream))
+    if check:
+        _check(rc, "knap_varlen_attn_bwd_noalloc")
     return rc
 
 

@@ -9,6 +9,12 @@
 #include <atomic>
 #include <mutex>
 
+// Scratch of knap_varlen_attn_bwd_noalloc: the per-row dot products of dout and out (fp32, (H, T)) and,
+// in the last 256 bytes, the work-queue counters of the dQ kernel.  Part of the library's device image:
+// every GPU the library runs on holds its own copy until the process ends.  Host code never uses this
+// name as an address; it uses the pointer hipGetSymbolAddress returned on that device (DeviceInfo::scratch).
+static __device__ __align__(256) unsigned char scratch[KNAP_NOALLOC_MAX_ROWS * sizeof(float) + 256];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -21,6 +27,7 @@ struct DeviceInfo {
   int dkdv_wg[2] = {0, 0};
   int dq_wg[2] = {0, 0};
   unsigned* fwd_queue = nullptr;   // this device's copy of the forward work-queue counters
+  unsigned char* scratch = nullptr;   // this device's copy of `scratch`
 };
 
 // Counter sets of the forward's work queue: the lower half is handed out in rotation to eager launches,
@@ -45,6 +52,12 @@ void fill_device_info(DeviceInfo& di, int dev) {
   di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
   di.fwd_queue = knap::fwd_queue_base();
   if (!di.fwd_queue) return;
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+    (void)hipGetLastError();
+    return;
+  }
+  di.scratch = static_cast<unsigned char*>(p);
   di.cus = cus;     // last: marks the entry as complete
 }
 
@@ -102,7 +115,7 @@ int fwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
 int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seq,
              int H, int d, float scale, bool causal,
              const void* out, const float* lse, const void* dout, void* dq, void* dk, void* dv,
-             int64_t total_tokens, void* workspace, size_t workspace_bytes, void* stream);
+             int64_t total_tokens, void* workspace, size_t workspace_bytes, bool own_scratch, void* stream);
 
 }  // namespace
 
@@ -137,7 +150,17 @@ int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          int64_t total_tokens,
                          void* workspace, size_t workspace_bytes, void* stream) {
   return bwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, false, out, lse, dout, dq, dk, dv, total_tokens,
-                  workspace, workspace_bytes, stream);
+                  workspace, workspace_bytes, false, stream);
+}
+
+int knap_varlen_attn_bwd_noalloc(const void* q, const void* k, const void* v,
+                                 const int32_t* cu_seqlens, int n_seq,
+                                 int H, int d, float scale,
+                                 const void* out, const float* lse, const void* dout,
+                                 void* dq, void* dk, void* dv,
+                                 int64_t total_tokens, void* stream) {
+  return bwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, false, out, lse, dout, dq, dk, dv, total_tokens,
+                  nullptr, 0, true, stream);
 }
 
 int knap_varlen_attn_causal_bwd(const void* q, const void* k, const void* v,
@@ -148,7 +171,7 @@ int knap_varlen_attn_causal_bwd(const void* q, const void* k, const void* v,
                                 int64_t total_tokens,
                                 void* workspace, size_t workspace_bytes, void* stream) {
   return bwd_impl(q, k, v, cu_seqlens, n_seq, H, d, scale, true, out, lse, dout, dq, dk, dv, total_tokens,
-                  workspace, workspace_bytes, stream);
+                  workspace, workspace_bytes, false, stream);
 }
 
 }  // extern "C"
@@ -158,10 +181,12 @@ namespace {
 int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seq,
              int H, int d, float scale, bool causal,
              const void* out, const float* lse, const void* dout, void* dq, void* dk, void* dv,
-             int64_t total_tokens, void* workspace, size_t workspace_bytes, void* stream) {
+             int64_t total_tokens, void* workspace, size_t workspace_bytes, bool own_scratch, void* stream) {
   const int rc = check_common(q, k, v, cu_seqlens, n_seq, H, d, scale);
   if (rc != KNAP_OK) return rc;
   if (total_tokens < 0 || total_tokens > INT32_MAX) return KNAP_ERR_INVALID_ARG;
+  // the library's own scratch holds one float per (row, head): larger bags are refused, whatever else is wrong
+  if (own_scratch && total_tokens * (int64_t)H > (int64_t)KNAP_NOALLOC_MAX_ROWS) return KNAP_ERR_SCRATCH_TOO_SMALL;
   if (n_seq == 0 || total_tokens == 0) return KNAP_OK;
   if (!out || !lse || !dout || !dq || !dk || !dv) return KNAP_ERR_INVALID_ARG;
   if (!aligned(out, 16) || !aligned(dout, 16) || !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) ||
@@ -169,10 +194,13 @@ int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
     return KNAP_ERR_INVALID_ARG;
   if (dq == dk || dq == dv || dk == dv || dq == q || dk == k || dv == v) return KNAP_ERR_INVALID_ARG;
   const size_t need = knap_varlen_attn_bwd_workspace_bytes(total_tokens, n_seq, H, d);
-  if (!workspace || !aligned(workspace, 256)) return KNAP_ERR_INVALID_ARG;
-  if (workspace_bytes < need) return KNAP_ERR_WORKSPACE_TOO_SMALL;
+  if (!own_scratch) {
+    if (!workspace || !aligned(workspace, 256)) return KNAP_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return KNAP_ERR_WORKSPACE_TOO_SMALL;
+  }
   DeviceInfo* di = device_info();
   if (!di) return KNAP_ERR_LAUNCH_FAILED;
+  if (own_scratch) workspace = di->scratch;     // carved exactly as a caller's workspace; need <= sizeof(scratch)
 
   float* delta = static_cast<float*>(workspace);
   unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
@@ -284,6 +312,7 @@ const char* knap_strerror(int code) {
     case KNAP_ERR_TOO_MANY_SEQS: return "too many sequences in one bag";
     case KNAP_ERR_CAPACITY: return "output array too small";
     case KNAP_ERR_PARSE: return "malformed topology string";
+    case KNAP_ERR_SCRATCH_TOO_SMALL: return "bag exceeds the library's own scratch (KNAP_NOALLOC_MAX_ROWS)";
     default: return "unknown error";
   }
 }
