@@ -84,9 +84,10 @@ int knap_varlen_attn_fwd(const void* q, const void* k, const void* v,
  * `workspace` is caller-owned device scratch of at least
  * knap_varlen_attn_bwd_workspace_bytes(total_tokens, n_seq, H, d) bytes,
  * 256-byte aligned; its contents on entry are ignored and on return are
- * unspecified.  It holds the per-row dot products of dout and out and the
- * counters of the kernels' work queues, so two calls that may run at the same
- * time (different streams) need a workspace each. */
+ * unspecified.  It holds the per-row dot products of dout and out, the
+ * log-sum-exp in base 2 and the counters of the kernels' work queues, so two
+ * calls that may run at the same time (different streams) need a workspace
+ * each. */
 int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
                          const int32_t* cu_seqlens, int n_seq,
                          int H, int d, float scale,
@@ -102,10 +103,11 @@ size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int
 /* knap_varlen_attn_bwd for callers that cannot allocate a workspace: code under
  * HIP graph capture, tight serving or training loops, harnesses that forbid
  * hipMalloc.  Same arguments without `workspace`, same kernels, same results
- * bit for bit.  The scratch (the per-row dot products of dout and out, one
- * float per (row, head), plus 256 bytes of work-queue counters) is an array in
- * the library's device image, KNAP_NOALLOC_MAX_ROWS floats + 256 bytes = 16 MiB
- * + 256 bytes that every GPU the library runs on holds until the process ends.
+ * bit for bit.  The scratch (the per-row dot products of dout and out and the
+ * log-sum-exp in base 2, two floats per (row, head), plus 256 bytes of
+ * work-queue counters) is an array in the library's device image,
+ * 2 * KNAP_NOALLOC_MAX_ROWS floats + 256 bytes = 32 MiB + 256 bytes that every
+ * GPU the library runs on holds until the process ends.
  * The call allocates and frees nothing and synchronises nothing.
  * Limit: total_tokens * H <= KNAP_NOALLOC_MAX_ROWS, else
  * KNAP_ERR_SCRATCH_TOO_SMALL (nothing is enqueued).

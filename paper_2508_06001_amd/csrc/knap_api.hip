@@ -9,11 +9,11 @@
 #include <atomic>
 #include <mutex>
 
-// Scratch of knap_varlen_attn_bwd_noalloc: the per-row dot products of dout and out (fp32, (H, T)) and,
-// in the last 256 bytes, the work-queue counters of the dQ kernel.  Part of the library's device image:
+// Scratch of knap_varlen_attn_bwd_noalloc: the per-row dot products of dout and out and the base-2
+// log-sum-exp (fp32, (H, T) each) and, in the last 256 bytes, the work-queue counters of the dQ kernel.  Part of the library's device image:
 // every GPU the library runs on holds its own copy until the process ends.  Host code never uses this
 // name as an address; it uses the pointer hipGetSymbolAddress returned on that device (DeviceInfo::scratch).
-static __device__ __align__(256) unsigned char scratch[KNAP_NOALLOC_MAX_ROWS * sizeof(float) + 256];
+static __device__ __align__(256) unsigned char scratch[2 * KNAP_NOALLOC_MAX_ROWS * sizeof(float) + 256];
 
 namespace {
 
@@ -25,6 +25,7 @@ struct DeviceInfo {
   int cus = 0;
   int fwd_wg[2] = {0, 0};   // workgroups per CU, index 0: d = 64, 1: d = 128
   int dkdv_wg[2] = {0, 0};
+  int dkdv_causal_wg[2] = {0, 0};
   int dq_wg[2] = {0, 0};
   unsigned* fwd_queue = nullptr;   // this device's copy of the forward work-queue counters
   unsigned char* scratch = nullptr;   // this device's copy of `scratch`
@@ -46,8 +47,10 @@ void fill_device_info(DeviceInfo& di, int dev) {
   }
   di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
   di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
-  di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64);
-  di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
+  di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64, false);
+  di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128, false);
+  di.dkdv_causal_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64, true);
+  di.dkdv_causal_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128, true);
   di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
   di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
   di.fwd_queue = knap::fwd_queue_base();
@@ -138,8 +141,8 @@ int knap_varlen_attn_causal_fwd(const void* q, const void* k, const void* v,
 size_t knap_varlen_attn_bwd_workspace_bytes(int64_t total_tokens, int n_seq, int H, int d) {
   (void)n_seq;
   if (total_tokens <= 0 || H <= 0 || d <= 0) return 0;
-  // delta, fp32 (H, T), then 256 bytes of work-queue counters
-  return round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256) + 256;
+  // delta and the base-2 log-sum-exp, fp32 (H, T) each, then 256 bytes of work-queue counters
+  return 2 * round_up(static_cast<size_t>(total_tokens) * H * sizeof(float), 256) + 256;
 }
 
 int knap_varlen_attn_bwd(const void* q, const void* k, const void* v,
@@ -203,11 +206,12 @@ int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
   if (own_scratch) workspace = di->scratch;     // carved exactly as a caller's workspace; need <= sizeof(scratch)
 
   float* delta = static_cast<float*>(workspace);
+  float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + (need - 256) / 2);
   unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
-  const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
+  const int grid_dkdv = di->cus * (causal ? di->dkdv_causal_wg[d == 128] : di->dkdv_wg[d == 128]);
   const int grid_dq = di->cus * di->dq_wg[d == 128];
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, causal, out, lse, dout,
-                                        dq, dk, dv, delta, counters, grid_dkdv, grid_dq,
+                                        dq, dk, dv, delta, lse2, counters, grid_dkdv, grid_dq,
                                         static_cast<hipStream_t>(stream), g_prof_start, g_prof_stop);
   if (e != hipSuccess) { g_last_hip_error = static_cast<int>(e); return KNAP_ERR_LAUNCH_FAILED; }
   return KNAP_OK;

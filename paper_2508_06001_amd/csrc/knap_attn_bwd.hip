@@ -341,6 +341,367 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// dK/dV kernel, bidirectional mask: 64 key rows per wave pair.
+//
+// Same roles as above (dV wave: S, P, dV; dK wave, one tile behind: dP, dS, dK), but a pair owns 64
+// key rows (two 32-row blocks) of a 256-row key/value tile and a step covers 32 query rows.  Every
+// fragment of Q or dO that a wave reads from LDS, row-wise for S / dP and transposed for dV / dK, then
+// feeds TWO MFMAs, one per key block: 512 bytes of LDS operand per MFMA instead of 1024.  The registers
+// just allow it because the accumulators sit on the key side: per wave 128 (dV or dK, 64 x d fp32) + 64
+// (its K or V rows) + 32 (scores of a step) + operands in flight, within the 256 of two waves per SIMD
+// (every base address in scalar registers, every LDS address formed next to its read).
+//
+// Query-side tiles (32 rows of Q and dO, their LSE in base 2 and delta) go global -> LDS
+// asynchronously, DEPTH tiles ahead, into a ring of DEPTH + 2 buffers (being filled / dV role / dK
+// role).  The buffers are separate arrays and the loop is unrolled once around the ring, so that every
+// LDS read names its buffer at compile time and is known not to depend on the copies in flight into
+// the others; the waits are exact (vector-memory operations complete in issue order, every wave
+// issues the same number per tile).  Rows past the end of the sequence arrive as zeros in all four
+// (empty buffer descriptor): P = exp2(0 - 0) = 1 there, but dO = 0 and dP - delta = 0, so they add
+// nothing to dV or dK.
+// ---------------------------------------------------------------------------
+template <int D>
+struct Bwd2Cfg {
+  static constexpr int THREADS = 512;
+  static constexpr int BM = 32;
+  static constexpr int BN = 256;
+  static constexpr int KB = 2;
+  static constexpr int NB = D / 32;
+  static constexpr int KC = D / 16;
+  static constexpr int DEPTH = 3;
+  static constexpr int NBUF = DEPTH + 2;
+  static constexpr int TILE_ELEMS = BM * Tile<D>::LD;
+  static constexpr int LOADS_PER_TILE = (D == 128 ? 2 : 1) + 1;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vm_loads() {
+  static_assert(N >= 0 && N < 64, "vmcnt is six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Readers with ONE base register each: the swizzle is an XOR on the chunk index, so the offset of
+// chunk pair cc of a row read is base ^ (32 cc) bytes-in-elements, and of (db, hi) of a transposing read
+// (base ^ (32 db + 16 hi)) + 8 hi rows.
+template <int D>
+struct RowReaderX {
+  int base;
+  __device__ __forceinline__ void init(int lane) { base = 2 * Tile<D>::off(lane & 31, 8 * (lane >> 5)); }   // bytes
+  // a copy of the base the optimizer cannot see through: what is derived from it stays in the step that
+  // uses it (an address hoisted out of the loop would need a register of its own per buffer and chunk,
+  // whereas formed next to its read the buffer's address becomes the read's immediate offset)
+  __device__ __forceinline__ int fresh() const { int b = base; asm volatile("" : "+v"(b)); return b; }
+  __device__ static __forceinline__ bf16x8 get(const __bf16* tile, int b, int cc) {
+    return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(tile) + (b ^ (32 * cc)));
+  }
+};
+template <int D>
+struct ColReaderX {
+  int base;
+  __device__ __forceinline__ void init(int lane) {
+    const int i = lane & 15, kr = i >> 2, hh = lane >> 5;
+    base = 2 * Tile<D>::off(4 * hh + kr, ((lane >> 4) & 1) * 16 + 4 * (i & 3));   // bytes
+  }
+  __device__ __forceinline__ int fresh() const { int b = base; asm volatile("" : "+v"(b)); return b; }
+  __device__ static __forceinline__ bf16x8 get(const __bf16* tile, int b, int k_base, int db) {
+    const char* p = reinterpret_cast<const char*>(tile + k_base * Tile<D>::LD);
+    // rows 8 further down: at D = 128 the swizzle flips bit 1 of the chunk position there, at D = 64 bit 2
+    // (the bit that db flips as well)
+    return join(lds_read_tr(reinterpret_cast<const __bf16*>(p + (b ^ (64 * db)))),
+                lds_read_tr(reinterpret_cast<const __bf16*>(p + ((b ^ (D == 128 ? 64 * db + 32 : 64 * (db ^ 1))) + 16 * Tile<D>::LD))));
+  }
+};
+
+template <int D>
+__global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel(
+    const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
+    const __bf16* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
+    const int32_t* __restrict__ cu, int n_seq, int H, float scale,
+    __bf16* __restrict__ dk, __bf16* __restrict__ dv) {
+  using C = Bwd2Cfg<D>;
+  extern __shared__ int s_dyn[];
+  int* s_order = s_dyn;
+  int* s_start = s_dyn + n_seq;
+#define KNAP_RING(i)                                                                    \
+  __shared__ __attribute__((aligned(1024))) __bf16 sQ##i[C::TILE_ELEMS];                \
+  __shared__ __attribute__((aligned(1024))) __bf16 sdO##i[C::TILE_ELEMS];               \
+  __shared__ __attribute__((aligned(256))) float sLse##i[64];                           \
+  __shared__ __attribute__((aligned(256))) float sDelta##i[64];
+  KNAP_RING(0) KNAP_RING(1) KNAP_RING(2) KNAP_RING(3) KNAP_RING(4)
+#undef KNAP_RING
+  __shared__ __attribute__((aligned(256))) float sSink[64];
+  __shared__ __attribute__((aligned(16))) u32x4 sP[4][2][2 * C::KB][64];
+
+  const int n_items = build_schedule<C::BN, C::THREADS, false>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
+  const int T = cu[n_seq];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int pair = wave & 3;
+  const int role = wave >> 2;
+  const int l32 = lane & 31;
+  const int hh = lane >> 5;
+  const float c = scale * kLog2e;
+  const size_t row_stride = (size_t)H * D;
+  const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
+  RowReaderX<D> rows;
+  ColReaderX<D> cols;
+  rows.init(lane);
+  cols.init(lane);
+
+  constexpr int ROWS_PER_INSTR = 512 / D;
+  const int cp_row0 = (D == 128 ? wave : (wave & 3)) * ROWS_PER_INSTR;
+  const int cp_row = cp_row0 + lane / Tile<D>::CPR;
+  const uint32_t cp_off = (uint32_t)cp_row * row_bytes + (uint32_t)Tile<D>::chunk_pos(cp_row, lane % Tile<D>::CPR) * 16u;
+
+  const int wg = xcd_major_block_id();
+  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
+    const int w = serpentine_item(round, wg, (int)gridDim.x);
+    if (w >= n_items) continue;
+    WorkItem it = decode_item<C::BN, false>(w, cu, n_seq, s_order, s_start);
+    // head and tile come out of a division, i.e. of vector instructions: say that they are wave-uniform, so
+    // that every base address below lives in scalar registers
+    it.head = __builtin_amdgcn_readfirstlane(it.head);
+    it.tile = __builtin_amdgcn_readfirstlane(it.tile);
+    const int L = it.len;
+    const size_t head_off = (size_t)it.head * D;
+    const int kv0 = it.tile * C::BN;
+    const __bf16* q_base = q + (size_t)it.row0 * row_stride + head_off;
+    const __bf16* do_base = dout + (size_t)it.row0 * row_stride + head_off;
+    const float* lse_base = lse2 + (size_t)it.head * T + it.row0;
+    const float* delta_base = delta + (size_t)it.head * T + it.row0;
+    const int n_tiles = (L + C::BM - 1) / C::BM;
+
+    __syncthreads();
+
+    bf16x8 kvf[C::KB][C::KC];
+    {
+      const uint32_t kv_bytes = (uint32_t)min(L - kv0, C::BN) * row_bytes;
+      const __bf16* src = (role == 0 ? k : v) + (size_t)(it.row0 + kv0) * row_stride + head_off;
+      const auto r = make_rsrc(src, kv_bytes);
+#pragma unroll
+      for (int kb = 0; kb < C::KB; ++kb) {
+        const uint32_t off = (uint32_t)(64 * pair + 32 * kb + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
+#pragma unroll
+        for (int cc = 0; cc < C::KC; ++cc) kvf[kb][cc] = __builtin_bit_cast(bf16x8, buffer_load16(r, off + 32u * cc));
+      }
+    }
+
+    f32x16 acc[C::KB][C::NB];
+#pragma unroll
+    for (int kb = 0; kb < C::KB; ++kb)
+#pragma unroll
+      for (int nb = 0; nb < C::NB; ++nb) acc[kb][nb] = zero16();
+
+    auto issue_tile = [&](int t, __bf16* tQ, __bf16* tdO, float* tLse, float* tDelta) {
+      const int q0 = t * C::BM;
+      const int n_rows = max(0, min(L - q0, C::BM));
+      const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, (uint32_t)n_rows * row_bytes);
+      const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, (uint32_t)n_rows * row_bytes);
+      if constexpr (D == 128) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, (__attribute__((address_space(3))) void*)(tQ + cp_row0 * Tile<D>::LD), 16, (int)cp_off, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (__attribute__((address_space(3))) void*)(tdO + cp_row0 * Tile<D>::LD), 16, (int)cp_off, 0, 0, 0);
+      } else {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wave < 4 ? rq : rd,
+            (__attribute__((address_space(3))) void*)((wave < 4 ? tQ : tdO) + cp_row0 * Tile<D>::LD), 16, (int)cp_off, 0, 0, 0);
+      }
+      const float* src = wave == 0 ? lse_base + q0 : delta_base + q0;
+      float* dst = wave == 0 ? tLse : wave == 1 ? tDelta : sSink;
+      const auto rs = make_rsrc(src, wave < 2 ? (uint32_t)n_rows * 4u : 0u);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)dst, 4, lane * 4, 0, 0, 0);
+    };
+
+    // End of a step: this wave's copies of the next tile have landed (all but the (DEPTH - 1) tiles requested
+    // after it), its LDS writes (P) are done, then the workgroup barrier.  A bare s_barrier: __syncthreads()
+    // would wait for EVERY copy in flight (its release fence covers the asynchronous LDS writes) and cut the
+    // prefetch distance to one tile.  The empty asm statements keep the compiler from moving LDS accesses
+    // across the barrier.
+    auto step_sync = [&]() {
+      wait_vm_loads<(C::DEPTH - 1) * C::LOADS_PER_TILE>();
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    };
+
+    // Both roles share one shape of step, written as an explicit software pipeline (scheduling fences
+    // between the groups, so that the order below is the order issued): LDS fragments are requested
+    // AHEAD groups before the MFMAs that use them, and the arithmetic of the second half of the tile
+    // (16 queries) is cut into slices that sit between the MFMAs of the first half.
+    constexpr int AHEAD = 2;
+    // first product: x[kb] = sum over d of tile rows (A, from LDS) x this wave's K or V rows (B, registers / LDS)
+    auto first_product = [&](const __bf16* tA, int rb, f32x16 (&x)[C::KB]) {
+      bf16x8 af[C::KC];
+#pragma unroll
+      for (int cc = 0; cc < AHEAD; ++cc) af[cc] = rows.get(tA, rb, cc);
+      KNAP_SCHED_FENCE();
+#pragma unroll
+      for (int cc = 0; cc < C::KC; ++cc) {
+#pragma unroll
+        for (int kb = 0; kb < C::KB; ++kb) x[kb] = mfma32(af[cc], kvf[kb][cc], x[kb]);
+        if (cc + AHEAD < C::KC) af[cc + AHEAD] = rows.get(tA, rb, cc + AHEAD);
+        KNAP_SCHED_FENCE();
+      }
+    };
+    // second product over the 16 queries of chunk cq: acc[kb][nb] += op[kb] (A, registers) x tile columns (B, LDS),
+    // with `between(nb)` issued after the MFMAs of column block nb
+    auto second_product = [&](const __bf16* tB, int cb, int cq, const bf16x8 (&op)[C::KB], auto between) {
+      bf16x8 bf[C::NB];
+      constexpr int AH2 = 2;
+#pragma unroll
+      for (int nb = 0; nb < AH2; ++nb) bf[nb] = cols.get(tB, cb, 16 * cq, nb);
+      KNAP_SCHED_FENCE();
+#pragma unroll
+      for (int nb = 0; nb < C::NB; ++nb) {
+#pragma unroll
+        for (int kb = 0; kb < C::KB; ++kb) acc[kb][nb] = mfma32(op[kb], bf[nb], acc[kb][nb]);
+        if (nb + AH2 < C::NB) bf[nb + AH2] = cols.get(tB, cb, 16 * cq, nb + AH2);
+        between(nb);
+        KNAP_SCHED_FENCE();
+      }
+    };
+
+    // dV wave, tile t: S, P, hand P over, dV += P^T dO
+    auto dv_step = [&](int t, const __bf16* tQ, const __bf16* tdO, const float* tLse) {
+      const int rb = rows.fresh(), cb = cols.fresh();
+      f32x16 s[C::KB];
+#pragma unroll
+      for (int kb = 0; kb < C::KB; ++kb) s[kb] = zero16();
+      first_product(tQ, rb, s);
+      // P = exp2(c S - LSE2); register r of a key block is query 8 (r / 4) + 4 hh + r % 4, chunk cq holds
+      // registers 8 cq .. 8 cq + 7, slice (kb, half) four of them
+      bf16x8 pa[2][C::KB];
+      bf16x4 ph[2][C::KB][2];
+      f32x4 lq[2][2];
+      auto lse_of = [&](int cq) {
+        lq[cq][0] = *reinterpret_cast<const f32x4*>(&tLse[16 * cq + 4 * hh]);
+        lq[cq][1] = *reinterpret_cast<const f32x4*>(&tLse[16 * cq + 8 + 4 * hh]);
+      };
+      auto exp_slice = [&](int cq, int kb, int half) {
+        float p[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = fast_exp2(__builtin_fmaf(s[kb][8 * cq + 4 * half + e], c, -lq[cq][half][e]));
+        ph[cq][kb][half] = pack4(p[0], p[1], p[2], p[3]);
+        if (half == 1) {
+          pa[cq][kb] = join(ph[cq][kb][0], ph[cq][kb][1]);
+          sP[pair][t & 1][2 * kb + cq][lane] = __builtin_bit_cast(u32x4, pa[cq][kb]);
+        }
+      };
+      lse_of(0);
+#pragma unroll
+      for (int j = 0; j < 2 * C::KB; ++j) exp_slice(0, j >> 1, j & 1);
+      lse_of(1);
+      KNAP_SCHED_FENCE();
+      second_product(tdO, cb, 0, pa[0], [&](int nb) {
+        // 2 KB slices of the second chunk spread over NB groups
+        if constexpr (C::NB == 4) exp_slice(1, nb >> 1, nb & 1);
+        else { exp_slice(1, nb, 0); exp_slice(1, nb, 1); }
+      });
+      second_product(tdO, cb, 1, pa[1], [&](int) {});
+    };
+    // dK wave, tile u: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
+    // dK wave, tile u: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
+    auto dk_step = [&](int u, const __bf16* tQ, const __bf16* tdO, const float* tDelta) {
+      const int rb = rows.fresh();
+      f32x16 dp[C::KB];
+#pragma unroll
+      for (int kb = 0; kb < C::KB; ++kb) dp[kb] = zero16();
+      first_product(tdO, rb, dp);
+      const int cb = cols.fresh();
+      bf16x8 da[2][C::KB];
+      bf16x4 dh[2][C::KB][2];
+      f32x4 dq4[2][2];
+      u32x4 pw[2][C::KB];
+      auto fetch_of = [&](int cq) {
+        dq4[cq][0] = *reinterpret_cast<const f32x4*>(&tDelta[16 * cq + 4 * hh]);
+        dq4[cq][1] = *reinterpret_cast<const f32x4*>(&tDelta[16 * cq + 8 + 4 * hh]);
+#pragma unroll
+        for (int kb = 0; kb < C::KB; ++kb) pw[cq][kb] = sP[pair][u & 1][2 * kb + cq][lane];
+      };
+      auto ds_slice = [&](int cq, int kb, int half) {
+        float ds[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t word = pw[cq][kb][2 * half + (e >> 1)];
+          const float p = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+          ds[e] = p * (dp[kb][8 * cq + 4 * half + e] - dq4[cq][half][e]);
+        }
+        dh[cq][kb][half] = pack4(ds[0], ds[1], ds[2], ds[3]);
+        if (half == 1) da[cq][kb] = join(dh[cq][kb][0], dh[cq][kb][1]);
+      };
+      fetch_of(0);
+#pragma unroll
+      for (int j = 0; j < 2 * C::KB; ++j) ds_slice(0, j >> 1, j & 1);
+      fetch_of(1);
+      KNAP_SCHED_FENCE();
+      second_product(tQ, cb, 0, da[0], [&](int nb) {
+        if constexpr (C::NB == 4) ds_slice(1, nb >> 1, nb & 1);
+        else { ds_slice(1, nb, 0); ds_slice(1, nb, 1); }
+      });
+      second_product(tQ, cb, 1, da[1], [&](int) {});
+    };
+
+    // Each role runs its own copy of the loop over the steps: with the roles as branches inside one
+    // loop the accumulators would be merged at every step's join, and the register allocator then keeps
+    // two sets.  Every wave still executes the same sequence of copies, waits and barriers.
+#define KNAP_STEP(ROLE, t, cur, prev, nxt)                                                    \
+    do {                                                                                      \
+      issue_tile((t) + C::DEPTH, sQ##nxt, sdO##nxt, sLse##nxt, sDelta##nxt);                  \
+      if constexpr (ROLE == 0) {                                                              \
+        if ((t) < n_tiles) dv_step((t), sQ##cur, sdO##cur, sLse##cur);                        \
+      } else {                                                                                \
+        if ((t) >= 1) dk_step((t) - 1, sQ##prev, sdO##prev, sDelta##prev);                    \
+      }                                                                                       \
+      step_sync();                                                                            \
+    } while (0)
+#define KNAP_ROLE_LOOP(ROLE)                                                                  \
+    do {                                                                                      \
+      int t = 0;                                                                              \
+      for (; t + 4 <= n_tiles; t += 5) {                                                      \
+        KNAP_STEP(ROLE, t, 0, 4, 3);                                                          \
+        KNAP_STEP(ROLE, t + 1, 1, 0, 4);                                                      \
+        KNAP_STEP(ROLE, t + 2, 2, 1, 0);                                                      \
+        KNAP_STEP(ROLE, t + 3, 3, 2, 1);                                                      \
+        KNAP_STEP(ROLE, t + 4, 4, 3, 2);                                                      \
+      }                                                                                       \
+      if (t <= n_tiles) {                                                                     \
+        KNAP_STEP(ROLE, t, 0, 4, 3);                                                          \
+        if (t + 1 <= n_tiles) {                                                               \
+          KNAP_STEP(ROLE, t + 1, 1, 0, 4);                                                    \
+          if (t + 2 <= n_tiles) {                                                             \
+            KNAP_STEP(ROLE, t + 2, 2, 1, 0);                                                  \
+            if (t + 3 <= n_tiles) KNAP_STEP(ROLE, t + 3, 3, 2, 1);                            \
+          }                                                                                   \
+        }                                                                                     \
+      }                                                                                       \
+    } while (0)
+
+    issue_tile(0, sQ0, sdO0, sLse0, sDelta0);
+    issue_tile(1, sQ1, sdO1, sLse1, sDelta1);
+    issue_tile(2, sQ2, sdO2, sLse2, sDelta2);
+    step_sync();      // tile 0 has landed (and the K / V rows requested before it)
+
+    if (role == 0) KNAP_ROLE_LOOP(0);
+    else KNAP_ROLE_LOOP(1);
+#undef KNAP_ROLE_LOOP
+#undef KNAP_STEP
+    wait_vm_loads<0>();
+
+    __bf16* dst = role == 0 ? dv : dk;
+    const float out_scale = role == 0 ? 1.0f : scale;
+#pragma unroll
+    for (int kb = 0; kb < C::KB; ++kb)
+#pragma unroll
+      for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kv0 + 64 * pair + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (kv < L)
+            dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[kb][nb][r] * out_scale);
+        }
+  }
+}
+
 template <int D>
 struct DqCfg {
   static constexpr int BM = 128;         // query rows per work item
@@ -354,7 +715,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ out, const __bf16* __restrict__ dout, const float* __restrict__ lse,
-    float* __restrict__ delta, const int32_t* __restrict__ cu, int n_seq, int H, float scale,
+    float* __restrict__ delta, float* __restrict__ lse2_out, const int32_t* __restrict__ cu, int n_seq, int H, float scale,
     __bf16* __restrict__ dq, unsigned* __restrict__ counters) {
   using C = DqCfg<D>;
   extern __shared__ int s_dyn[];
@@ -439,7 +800,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
     const int q_idx = q_valid ? q_row : 0;
     const float lse_raw = lse[(size_t)it.head * T + it.row0 + q_idx];
     const float lse2 = q_valid ? lse_raw * kLog2e : INFINITY;
-    if (q_valid && hh == 0) delta[(size_t)it.head * T + it.row0 + q_row] = dl;
+    if (q_valid && hh == 0) {     // for the dK/dV kernel: delta, and the LSE in base 2 (it copies both straight into LDS)
+      delta[(size_t)it.head * T + it.row0 + q_row] = dl;
+      lse2_out[(size_t)it.head * T + it.row0 + q_row] = lse_raw * kLog2e;
+    }
 
     f32x16 acc[C::DB];
 #pragma unroll
@@ -571,7 +935,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(
 template <int D, bool CAUSAL>
 static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H,
                                float scale, const void* out, const float* lse, const void* dout,
-                               void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                               void* dq, void* dk, void* dv, float* delta, float* lse2, unsigned* counters,
                                int grid_dkdv, int grid_dq, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
   hipLaunchKernelGGL(bwd_queue_reset_kernel, dim3(1), dim3(64), 0, stream, counters);
@@ -581,13 +945,19 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   // the dQ kernel also produces delta, which the dK/dV kernel needs: it goes first
   hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL>), dim3(grid_dq), dim3(kThreads), dyn, stream,
                      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)out,
-                     (const __bf16*)dout, lse, delta, cu, n_seq, H, scale, (__bf16*)dq, counters);
+                     (const __bf16*)dout, lse, delta, lse2, cu, n_seq, H, scale, (__bf16*)dq, counters);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
-                     (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
-                     (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
+  if constexpr (CAUSAL) {
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, true>), dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
+                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
+                       (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
+  } else {
+    hipLaunchKernelGGL((attn_bwd_dkdv64_kernel<D>), dim3(grid_dkdv), dim3(Bwd2Cfg<D>::THREADS), dyn, stream,
+                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout,
+                       (const float*)lse2, (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
@@ -596,10 +966,10 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, bool causal, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                      void* dq, void* dk, void* dv, float* delta, float* lse2, unsigned* counters,
                       int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop) {
-#define KNAP_BWD_ARGS q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, counters, \
+#define KNAP_BWD_ARGS q, k, v, cu, n_seq, H, scale, out, lse, dout, dq, dk, dv, delta, lse2, counters, \
                       grid_dkdv, grid_dq, stream, ev_start, ev_stop
   if (causal) return d == 64 ? launch_bwd_t<64, true>(KNAP_BWD_ARGS) : launch_bwd_t<128, true>(KNAP_BWD_ARGS);
   return d == 64 ? launch_bwd_t<64, false>(KNAP_BWD_ARGS) : launch_bwd_t<128, false>(KNAP_BWD_ARGS);
@@ -615,9 +985,12 @@ static int occupancy_of(const void* fn, int threads = kThreads) {
   return n;
 }
 
-int bwd_dkdv_workgroups_per_cu(int d) {
-  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64, false> : (const void*)attn_bwd_dkdv_kernel<128, false>,
-                      BwdCfg<128>::THREADS);
+int bwd_dkdv_workgroups_per_cu(int d, bool causal) {
+  if (causal)
+    return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64, true> : (const void*)attn_bwd_dkdv_kernel<128, true>,
+                        BwdCfg<128>::THREADS);
+  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv64_kernel<64> : (const void*)attn_bwd_dkdv64_kernel<128>,
+                      Bwd2Cfg<128>::THREADS);
 }
 
 int bwd_dq_workgroups_per_cu(int d) {

@@ -17,7 +17,7 @@ int fwd_queue_slots();
 
 hipError_t launch_bwd(const void* q, const void* k, const void* v, const int32_t* cu, int n_seq, int H, int d,
                       float scale, bool causal, const void* out, const float* lse, const void* dout,
-                      void* dq, void* dk, void* dv, float* delta, unsigned* counters,
+                      void* dq, void* dk, void* dv, float* delta, float* lse2, unsigned* counters,
                       int grid_dkdv, int grid_dq, hipStream_t stream,
                       hipEvent_t ev_start, hipEvent_t ev_stop);
 
@@ -32,7 +32,7 @@ hipError_t launch_ulysses_plan(const int32_t* cu, int n_seq, int g, int T, int32
 
 // resident workgroups per compute unit of the persistent kernels
 int fwd_workgroups_per_cu(int d);
-int bwd_dkdv_workgroups_per_cu(int d);
+int bwd_dkdv_workgroups_per_cu(int d, bool causal);
 int bwd_dq_workgroups_per_cu(int d);
 
 }  // namespace knap
