@@ -385,6 +385,55 @@ def run_default(args):
     print(json.dumps(out), flush=True)
 
 
+def run_sim(args):
+    """Second workload: the paper's own simulator streams (Sec. 4.1 data codes; the `joint` and `mixed_res`
+    workloads of Table 1 on 32 GPUs at 24 heads of 128).  The cost model is fitted on single-length bags in this
+    run, the library's greedy balancer forms 32 one-GPU bags per workload with it, every fourth bag is timed
+    (K steps each) and compared with the model.  `value` is the FLOPs of all timed bags over their total time."""
+    import torch
+    import paper_2508_06001_amd as K
+    from knap_inputs import BagSpec, table1_streams
+    ev = HipEvents()
+    H, d = 24, 128
+    a, b, cal_resid, rows = calibrate_model(H, d, 65536, ev)
+    log(f"[sim] model H={H} d={d}: a={a:.4e} ms/token^2 b={b:.4e} ms/token (calibration residual <= {100 * cal_resid:.1f} %)")
+    bags_out, tot_flops, tot_ms = [], 0.0, 0.0
+    for wl, seed in (("mixed_res", 31), ("joint", 32)):
+        pool = [L for g in table1_streams(wl, seed) for L in g]
+        bag_of, load = K.knap_greedy_assign(pool, [1] * 32, a, b)
+        for j in range(0, 32, 4):
+            lens, _ = K.knap_bag_cu_seqlens(pool, bag_of, j)
+            if not lens:
+                continue
+            bag = BagSpec(f"{wl}_bag{j}", lens, H=H, d=d, seed=9000 + j)
+            dev = [device_inputs_fast(bag), device_inputs_fast(bag, seed=1)]
+            r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev)
+            ms = r["gpu_ms_per_step"]
+            fl = flops_fwd(bag) + flops_bwd(bag)
+            pred = a * bag.sum_l2 + b * bag.total_tokens
+            bags_out.append({"workload": wl, "bag": j, "n_seq": len(lens), "total_tokens": bag.total_tokens,
+                             "max_len": max(lens), "ms_per_step": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                             "model_ms": round(pred, 4), "model_rel_resid": round(abs(ms - pred) / ms, 4)})
+            log(f"[sim] {wl} bag {j}: {len(lens)} seqs, {bag.total_tokens} tokens (max {max(lens)}): {ms:.3f} ms = "
+                f"{fl / ms / 1e9:.1f} TF/s; model {pred:.3f} ms, residual {100 * abs(ms - pred) / ms:.1f} %")
+            tot_flops += fl
+            tot_ms += ms
+            del dev, r
+            torch.cuda.empty_cache()
+    value = tot_flops / tot_ms / 1e9
+    out = {"metric": "varlen attention fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak", "value": round(value, 3),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(tot_ms / max(1, len(bags_out)), 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "paper simulator streams (Sec. 4.1: mixed_res and joint on 32 GPUs), one-GPU bags "
+                                  "formed by knap_greedy_assign, every fourth bag timed", "H": H, "d": d,
+                      "bags_timed": len(bags_out)},
+           "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+           "model": {"a_ms_per_token2": a, "b_ms_per_token": b, "calibration_max_rel_resid": round(cal_resid, 4)},
+           "max_model_rel_resid": max(x["model_rel_resid"] for x in bags_out), "bags": bags_out}
+    print(json.dumps(out), flush=True)
+
+
 def run_fit(args):
     """Cost-model experiment (Sec. 3.1 / Fig. 2 analogue): fit a, b of t = a sum(L^2) + b sum(L) by
     relative least squares (the library's knap_fit_cost_model), then report the relative residual of
@@ -393,8 +442,8 @@ def run_fit(args):
     Calibration bags hold n equal sequences with n L close to the token count of the bag family
     (65536 tokens for H = 24, 196608 for H = 3): the model prices a sequence inside a full bag, so the
     calibration has to fill the GPU too (a single short sequence measures launch latency instead).
-    Half of the random mixed bags join the calibration set; the benchmark bags and the other half are
-    predicted out of sample."""
+    Only those single-length bags enter the fit; the benchmark bags and every random draw are predicted
+    out of sample.  A fit with an intercept is reported beside it as a diagnostic."""
     import torch
     import paper_2508_06001_amd as K
     from knap_inputs import BagSpec, config_bag
@@ -433,9 +482,7 @@ def run_fit(args):
             log(f"[fit] {fam} {n} x L={L}: {rows[-1]['ms']:.3f} ms, {rows[-1]['tflops']:.1f} TF/s")
             del dev, r
             torch.cuda.empty_cache()
-        # every further bag is measured first; the odd-numbered draws then join the calibration set (bags of
-        # equal lengths alone run a few per cent more efficiently than mixed ones and would bias the model
-        # low), the benchmark bags (draw 0) and the even-numbered draws are predicted out of sample
+        # the benchmark bags (draw 0) and further random draws of the same families: all out of sample
         evals = []
         cfgs = {"H24_d128": [1, 2, 3], "H3_d128": [4], "H12_d64": [1, 2], "H24_d128_causal": [1, 2]}[fam]
         for ci in cfgs:
@@ -460,24 +507,31 @@ def run_fit(args):
                 dev = device_inputs_fast(bag)
                 r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev, causal=causal)
                 evals.append({"config": ci, "seed_offset": so, "n_seq": len(bag.seq_lens), "T": bag.total_tokens,
-                              "sum_l2": bag.sum_l2, "ms": r["gpu_ms_per_step"], "role": "calibration" if so % 2 else "evaluation"})
+                              "sum_l2": bag.sum_l2, "ms": r["gpu_ms_per_step"], "role": "evaluation"})
                 log(f"[fit] {fam} cfg{ci}/{so}: measured {r['gpu_ms_per_step']:.3f} ms")
                 del dev, r
                 torch.cuda.empty_cache()
-        cal = [e for e in evals if e["role"] == "calibration"]
-        s2 = [float(r["n"]) * float(r["L"]) ** 2 for r in rows] + [float(e["sum_l2"]) for e in cal]
-        s1 = [float(r["n"]) * float(r["L"]) for r in rows] + [float(e["T"]) for e in cal]
-        t = [r["ms"] for r in rows] + [e["ms"] for e in cal]
+        # Sec. 3.1 / Fig. 2 procedure: a and b come from the single-length bags alone; every benchmark bag and every
+        # random draw is predicted out of sample
+        s2 = [float(r["n"]) * float(r["L"]) ** 2 for r in rows]
+        s1 = [float(r["n"]) * float(r["L"]) for r in rows]
+        t = [r["ms"] for r in rows]
         a, b, resid = K.knap_fit_cost_model(s2, s1, t)
+        # diagnostic: the same relative least squares with an intercept c (a fixed cost per launch)
+        A3 = np.array([[x2 / ti, x1 / ti, 1.0 / ti] for x2, x1, ti in zip(s2, s1, t)])
+        a3, b3, c3 = np.linalg.lstsq(A3, np.ones(len(t)), rcond=None)[0]
         log(f"[fit] {fam}: a = {a:.4e} ms/token^2, b = {b:.4e} ms/token, calibration max residual {resid * 100:.1f}% "
-            f"({len(rows)} equal-length bags + {len(cal)} mixed bags)")
+            f"({len(rows)} single-length bags); with intercept: a = {a3:.4e}, b = {b3:.4e}, c = {c3 * 1e3:.1f} us")
         for e in evals:
+            e["role"] = "evaluation"
             e["pred_ms"] = a * e["sum_l2"] + b * e["T"]
             e["rel_resid"] = abs(e["ms"] - e["pred_ms"]) / e["ms"]
-            if e["role"] == "evaluation":
-                log(f"[fit] {fam} cfg{e['config']}/{e['seed_offset']}: measured {e['ms']:.3f} ms, model {e['pred_ms']:.3f} ms, "
-                    f"resid {e['rel_resid'] * 100:.1f}%")
+            e["pred_ms_with_intercept"] = a3 * e["sum_l2"] + b3 * e["T"] + c3
+            e["rel_resid_with_intercept"] = abs(e["ms"] - e["pred_ms_with_intercept"]) / e["ms"]
+            log(f"[fit] {fam} cfg{e['config']}/{e['seed_offset']}: measured {e['ms']:.3f} ms, model {e['pred_ms']:.3f} ms, "
+                f"resid {e['rel_resid'] * 100:.1f}% (with intercept {e['rel_resid_with_intercept'] * 100:.1f}%)")
         report["families"][fam] = {"a_ms_per_token2": a, "b_ms_per_token": b, "calibration_max_rel_resid": resid,
+                                   "with_intercept": {"a": float(a3), "b": float(b3), "c_ms": float(c3)},
                                    "calibration": rows, "evaluation": evals}
         if fam == "H24_d128":
             # The paper's own simulator workloads (Sec. 4.1, Table 1: FLUX has 24 heads of 128): the 32 GPUs'
@@ -675,6 +729,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle work for cpu_baseline")
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
+    ap.add_argument("--sim", action="store_true",
+                    help="time one-GPU bags drawn from the paper's simulator streams (second workload, not the headline)")
     ap.add_argument("--ulysses", action="store_true",
                     help="time the local data movement around the Ulysses all-to-alls (not the headline workload)")
     ap.add_argument("--fit-draws", type=int, default=12, help="evaluation bags per benchmark configuration in --fit")
@@ -693,6 +749,8 @@ def main():
     torch.cuda.set_device(0)
     if args.fit:
         run_fit(args)
+    elif args.sim:
+        run_sim(args)
     elif args.ulysses:
         run_ulysses(args)
     else:
