@@ -345,7 +345,7 @@ def run_default(args):
         "ms_per_step_median": round(r["step_ms_median"], 4), "ms_per_step_min": round(r["step_ms_min"], 4),
         "fwd_ms_median": round(r["fwd_ms_median"], 4), "bwd_ms_median": round(r["bwd_ms_median"], 4),
         "input_sets": 2,
-        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv64_kernel" if not causal else "attn_bwd_dkdv_kernel",
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv64_kernel",
                      "achieved": round(m["bwd_main_tflops"], 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(m["bwd_main_tflops"] / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_ms": round(r["bwd_main_ms"], 4),

@@ -25,7 +25,6 @@ struct DeviceInfo {
   int cus = 0;
   int fwd_wg[2] = {0, 0};   // workgroups per CU, index 0: d = 64, 1: d = 128
   int dkdv_wg[2] = {0, 0};
-  int dkdv_causal_wg[2] = {0, 0};
   int dq_wg[2] = {0, 0};
   unsigned* fwd_queue = nullptr;   // this device's copy of the forward work-queue counters
   unsigned char* scratch = nullptr;   // this device's copy of `scratch`
@@ -47,10 +46,8 @@ void fill_device_info(DeviceInfo& di, int dev) {
   }
   di.fwd_wg[0] = knap::fwd_workgroups_per_cu(64);
   di.fwd_wg[1] = knap::fwd_workgroups_per_cu(128);
-  di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64, false);
-  di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128, false);
-  di.dkdv_causal_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64, true);
-  di.dkdv_causal_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128, true);
+  di.dkdv_wg[0] = knap::bwd_dkdv_workgroups_per_cu(64);
+  di.dkdv_wg[1] = knap::bwd_dkdv_workgroups_per_cu(128);
   di.dq_wg[0] = knap::bwd_dq_workgroups_per_cu(64);
   di.dq_wg[1] = knap::bwd_dq_workgroups_per_cu(128);
   di.fwd_queue = knap::fwd_queue_base();
@@ -208,7 +205,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seql
   float* delta = static_cast<float*>(workspace);
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + (need - 256) / 2);
   unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + need - 256);
-  const int grid_dkdv = di->cus * (causal ? di->dkdv_causal_wg[d == 128] : di->dkdv_wg[d == 128]);
+  const int grid_dkdv = di->cus * di->dkdv_wg[d == 128];
   const int grid_dq = di->cus * di->dq_wg[d == 128];
   const hipError_t e = knap::launch_bwd(q, k, v, cu_seqlens, n_seq, H, d, scale, causal, out, lse, dout,
                                         dq, dk, dv, delta, lse2, counters, grid_dkdv, grid_dq,

@@ -16,8 +16,8 @@
 // dP: seven contractions are issued for the five the mathematics needs, nothing
 // is reduced across workgroups, and the result is bitwise reproducible.
 //
-// dK/dV kernel: a persistent workgroup of 8 waves owns a 128-row key/value tile of one (sequence,
-// head) and walks over that sequence's queries 64 rows at a time; wave pairs split the work by
+// dK/dV kernel: a persistent workgroup of 8 waves owns a 256-row key/value tile of one (sequence,
+// head) and walks over that sequence's queries 32 rows at a time; wave pairs split the work by
 // output (one wave S, P, dV; its partner dP, dS, dK, one tile behind) so that each wave holds a
 // single accumulator and two waves fit on a SIMD.  Details at the kernel.
 //
@@ -31,18 +31,6 @@
 
 namespace knap {
 
-template <int D>
-struct BwdCfg {
-  static constexpr int THREADS = 512;      // 8 waves: 4 key blocks x 2 roles
-  static constexpr int BM = 64;            // query rows per step
-  static constexpr int BN = 128;           // key/value rows per workgroup
-  static constexpr int MB = BM / 32;
-  static constexpr int NB = D / 32;
-  static constexpr int KC = D / 16;
-  static constexpr int NBUF = 3;           // ring of query-side tiles: being loaded / dV role / dK role
-  static constexpr int TILE_ELEMS = BM * Tile<D>::LD;   // Q / dO tiles: read both row-wise and transposed
-};
-
 constexpr int kQueueCounters = 8;    // one work-queue counter per XCD for the dQ kernel
 
 // the work queue of the dQ kernel, which follows on the stream, starts at zero
@@ -50,307 +38,25 @@ __global__ void bwd_queue_reset_kernel(unsigned* __restrict__ counters) {
   if (threadIdx.x < kQueueCounters) counters[threadIdx.x] = 0u;
 }
 
-// dK/dV kernel.  A workgroup of 8 waves owns a 128-row key/value tile of one (sequence, head) and
-// walks over that sequence's queries 64 rows at a time.  The waves form 4 pairs, pair i owning key
-// rows [32 i, 32 i + 32); the two waves of a pair (placed on the same SIMD) split the work by output:
+// ---------------------------------------------------------------------------
+// dK/dV kernel.  A persistent workgroup of 8 waves owns a 256-row key/value tile of one (sequence,
+// head) and walks over that sequence's queries 32 rows at a time.  The waves form 4 pairs, pair i
+// owning key rows [64 i, 64 i + 64) as two 32-row blocks; the two waves of a pair (placed on the same
+// SIMD) split the work by output:
 //   dV wave: keeps its K rows in registers, S = Q K^T, P = exp2(c S - LSE2), dV += P^T dO, and hands
-//            the packed bf16 P to its partner through LDS;
+//            the packed bf16 P to its partner through LDS (one way, double buffered);
 //   dK wave: keeps its V rows in registers and runs ONE TILE BEHIND: dP = dO V^T, dS = P (dP - delta)
 //            with the partner's P, dK += dS^T Q.
-// Each wave holds one 32 x d fp32 accumulator, so two waves fit on a SIMD and each one's MFMAs run
-// against the other's exponentials, LDS reads and waits.  With S = Q K^T in the MFMA result layout a
-// lane holds one key and its registers run over queries, so P and dS are, unchanged, the A operands
-// of the second products; dO and Q enter those through transposing LDS reads.  The exchange is one
-// way (dV wave -> dK wave, double buffered) and the query-side tiles live in a ring of three
-// buffers, so one workgroup barrier per tile covers every hand-over.
+// Each wave holds one accumulator, so two waves fit on a SIMD and each one's MFMAs run against the
+// other's exponentials, LDS reads and waits.  With S = Q K^T in the MFMA result layout a lane holds one
+// key and its registers run over queries, so P and dS are, unchanged, the A operands of the second
+// products; dO and Q enter those through transposing LDS reads.
 //
-// CAUSAL (query i sees keys 0..i): a key tile starting at row kv0 only meets the queries from row kv0
-// on.  The walk over them runs BACKWARDS, from the sequence's last query tile down to the two tiles that
-// cross the diagonal (which get the mask): workgroups on different key tiles of one (sequence, head)
-// then read the same query tiles at the same time, as they do without the mask, instead of each
-// starting at its own diagonal.  Work items are pairs of key tiles of equal total cost (see
-// build_schedule).
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
-    const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-    const __bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
-    const int32_t* __restrict__ cu, int n_seq, int H, float scale,
-    __bf16* __restrict__ dk, __bf16* __restrict__ dv) {
-  using C = BwdCfg<D>;
-  extern __shared__ int s_dyn[];
-  int* s_order = s_dyn;
-  int* s_start = s_dyn + n_seq;
-  __shared__ __attribute__((aligned(16))) __bf16 sQ[C::NBUF][C::TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) __bf16 sdO[C::NBUF][C::TILE_ELEMS];
-  __shared__ __attribute__((aligned(16))) float sLse[C::NBUF][C::BM];     // LSE in base 2; +inf for rows past the end
-  __shared__ __attribute__((aligned(16))) float sDelta[C::NBUF][C::BM];
-  __shared__ __attribute__((aligned(16))) u32x4 sP[4][2][2 * C::MB][64];  // [pair][parity][chunk of 16 queries][lane]
-  static_assert(sizeof(sP) >= sizeof(int) * C::THREADS, "scan scratch must fit in the exchange buffer");
-
-  const int n_items = build_schedule<C::BN, C::THREADS, CAUSAL>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
-  const int T = cu[n_seq];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int pair = wave & 3;        // key block; waves w and w + 4 share a SIMD
-  const int role = wave >> 2;       // 0: dV wave, 1: dK wave
-  const int l32 = lane & 31;
-  const int hh = lane >> 5;
-  const float c = scale * kLog2e;
-  const size_t row_stride = (size_t)H * D;
-  const uint32_t row_bytes = (uint32_t)(row_stride * sizeof(__bf16));
-
-  constexpr int TPR = D / 8;                         // 16-byte chunks per row
-  constexpr int RPP = C::THREADS / TPR;              // rows per pass
-  constexpr int NP = C::BM / RPP;                    // 16-byte loads per thread and tensor per tile
-  const int ld_row = tid / TPR;
-  const int ld_col = (tid % TPR) * 8;
-  RowReader<D> rows;     // Q / dO tile rows -> A operands of S / dP
-  ColReader<D> cols;     // dO / Q tile columns -> B operands of dV += P^T dO / dK += dS^T Q
-  rows.init(lane);
-  cols.init(lane);
-
-  // static assignment: measured, the dynamic queue the dQ kernel uses does not pay here
-  const int wg = xcd_major_block_id();
-  for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
-    const int w = serpentine_item(round, wg, (int)gridDim.x);
-    if (w >= n_items) continue;
-    const WorkItem it = decode_item<C::BN, CAUSAL>(w, cu, n_seq, s_order, s_start);
-    const int L = it.len;
-    const size_t head_off = (size_t)it.head * D;
-    // CAUSAL: the item is the pair of key tiles {p, kv_tiles - 1 - p}, the one with more queries first
-    const int kv_tiles = (L + C::BN - 1) / C::BN;
-    int sub = 0;
-  second_tile_of_pair:;     // CAUSAL only: jumped back to once, from the end of the first tile
-    const int kv_tile = !CAUSAL ? it.tile : sub == 0 ? it.tile : kv_tiles - 1 - it.tile;
-    const int kv0 = kv_tile * C::BN;
-    // queries this key tile meets: rows q_first .. L - 1 of the sequence; the walk below counts its
-    // tiles and rows from q_first
-    const int q_first = CAUSAL ? kv0 : 0;
-    const int Lq = L - q_first;
-    const __bf16* q_base = q + (size_t)(it.row0 + q_first) * row_stride + head_off;
-    const __bf16* do_base = dout + (size_t)(it.row0 + q_first) * row_stride + head_off;
-    const float* lse_base = lse + (size_t)it.head * T + it.row0 + q_first;
-    const float* delta_base = delta + (size_t)it.head * T + it.row0 + q_first;
-
-    // this wave's 32 key rows of K (dV wave) or V (dK wave) as B operands; rows past the end read as zero
-    bf16x8 kvf[C::KC];
-    {
-      const uint32_t kv_bytes = (uint32_t)min(L - kv0, C::BN) * row_bytes;
-      const __bf16* src = (role == 0 ? k : v) + (size_t)(it.row0 + kv0) * row_stride + head_off;
-      const auto r = make_rsrc(src, kv_bytes);
-      const uint32_t off = (uint32_t)(32 * pair + l32) * row_bytes + (uint32_t)(8 * hh) * 2u;
-#pragma unroll
-      for (int cc = 0; cc < C::KC; ++cc) kvf[cc] = __builtin_bit_cast(bf16x8, buffer_load16(r, off + 32u * cc));
-    }
-
-    f32x16 acc[C::NB];     // dV (dV wave) or dK (dK wave) rows of this pair
-#pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb) acc[nb] = zero16();
-
-    const int n_tiles = (Lq + C::BM - 1) / C::BM;
-
-    // A query-side tile travels global -> registers -> LDS.  Under load a tile's loads take longer
-    // than one step's arithmetic, so TWO tiles are kept in flight: tile t + 2 is requested at the
-    // top of step t into one register set while tile t + 1, requested a step earlier into the
-    // other set, is written to LDS at the bottom of step t.
-    struct Staged {
-      u32x4 q[NP], d[NP];
-      float lse, delta;
-      bool ok;
-    };
-    Staged stA, stB;       // tiles of even / odd index
-
-    // nothing here may wait for a load: the data is first touched in commit_tile
-    auto fetch_tile = [&](int t, Staged& st) {
-      // step t works on query tile t, or (CAUSAL) on tile n_tiles - 1 - t; both counted from q_first
-      const int q0 = (CAUSAL ? n_tiles - 1 - t : t) * C::BM;
-      const uint32_t bytes = (uint32_t)((CAUSAL && t >= n_tiles) ? 0 : max(0, min(Lq - q0, C::BM))) * row_bytes;   // past the end: zeros
-      const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, bytes);
-      const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, bytes);
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const uint32_t off = (uint32_t)(p * RPP + ld_row) * row_bytes + (uint32_t)ld_col * 2u;
-        st.q[p] = buffer_load16(rq, off);
-        st.d[p] = buffer_load16(rd, off);
-      }
-      const int r = tid & (C::BM - 1);          // every row is fetched by THREADS / BM threads
-      st.ok = q0 + r < Lq && !(CAUSAL && t >= n_tiles);
-      const int qi = st.ok ? q0 + r : 0;
-      st.lse = lse_base[qi];
-      st.delta = delta_base[qi];
-    };
-    auto commit_tile = [&](int buf, const Staged& st) {      // registers -> LDS
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const int o_ = Tile<D>::off(p * RPP + ld_row, ld_col);
-        *reinterpret_cast<u32x4*>(&sQ[buf][o_]) = st.q[p];
-        *reinterpret_cast<u32x4*>(&sdO[buf][o_]) = st.d[p];
-      }
-      sLse[buf][tid & (C::BM - 1)] = st.ok ? st.lse * kLog2e : INFINITY;   // +inf makes P = 0 on rows past the end
-      sDelta[buf][tid & (C::BM - 1)] = st.ok ? st.delta : 0.f;
-    };
-
-    // dV wave, tile t in buffer b: S, P, hand P over, dV += P^T dO
-    // (DIAG: the tile crosses the causal diagonal; a query before this lane's key gets P = 0)
-    auto dv_step = [&](auto diag_tag, int t, int b) {
-      constexpr bool DIAG = decltype(diag_tag)::value;
-      const __bf16* tQ = sQ[b];
-      const __bf16* tdO = sdO[b];
-      f32x16 s[C::MB];
-#pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb) {
-        s[mb] = zero16();
-#pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) s[mb] = mfma32(rows.get(tQ, 32 * mb, cc), kvf[cc], s[mb]);
-      }
-      KNAP_STREAM_READS(C::MB * C::KC, 1, 4);
-      KNAP_SCHED_FENCE();
-      // P = exp2(c S - LSE2); register r of block mb is query 32 mb + 8 (r / 4) + 4 hh + r % 4; packed so
-      // that element e of chunk cq is query 16 cq + 8 (e / 4) + 4 hh + e % 4
-      bf16x8 pa[2 * C::MB];
-      // counted from the tile's first query, this lane's key is the first one that query `first_seen` sees
-      const int first_seen = 32 * pair + l32 - (n_tiles - 1 - t) * C::BM - 4 * hh;
-#pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb) {
-        float p[16];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sLse[b][32 * mb + 8 * g + 4 * hh]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float pe = fast_exp2(__builtin_fmaf(s[mb][4 * g + e], c, -l4[e]));
-            p[4 * g + e] = (DIAG && 32 * mb + 8 * g + e < first_seen) ? 0.f : pe;
-          }
-        }
-        pa[2 * mb] = pack8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
-        pa[2 * mb + 1] = pack8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
-      }
-#pragma unroll
-      for (int cq = 0; cq < 2 * C::MB; ++cq) sP[pair][t & 1][cq][lane] = __builtin_bit_cast(u32x4, pa[cq]);
-      KNAP_SCHED_FENCE();
-#pragma unroll
-      for (int cq = 0; cq < 2 * C::MB; ++cq)
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) acc[nb] = mfma32(pa[cq], cols.get(tdO, 16 * cq, nb), acc[nb]);
-      KNAP_STREAM_READS(2 * C::MB * C::NB, 2, 3);
-      KNAP_SCHED_FENCE();
-    };
-    // dK wave, tile u in buffer b: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
-    auto dk_step = [&](int u, int b) {
-      const __bf16* tQ = sQ[b];
-      const __bf16* tdO = sdO[b];
-      f32x16 dp[C::MB];
-#pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb) {
-        dp[mb] = zero16();
-#pragma unroll
-        for (int cc = 0; cc < C::KC; ++cc) dp[mb] = mfma32(rows.get(tdO, 32 * mb, cc), kvf[cc], dp[mb]);
-      }
-      u32x4 pw[2 * C::MB];
-#pragma unroll
-      for (int cq = 0; cq < 2 * C::MB; ++cq) pw[cq] = sP[pair][u & 1][cq][lane];
-      KNAP_STREAM_READS(C::MB * C::KC, 1, 4);
-      KNAP_SCHED_FENCE();
-      bf16x8 da[2 * C::MB];
-#pragma unroll
-      for (int mb = 0; mb < C::MB; ++mb) {
-        float ds[16];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sDelta[b][32 * mb + 8 * g + 4 * hh]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;                       // register r <-> element r % 8 of chunk 2 mb + r / 8
-            const uint32_t word = pw[2 * mb + (r >> 3)][(r & 7) >> 1];
-            const float p = __builtin_bit_cast(float, (r & 1) ? (word & 0xffff0000u) : (word << 16));
-            ds[r] = p * (dp[mb][r] - d4[e]);
-          }
-        }
-        da[2 * mb] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
-        da[2 * mb + 1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
-      }
-      KNAP_SCHED_FENCE();
-#pragma unroll
-      for (int cq = 0; cq < 2 * C::MB; ++cq)
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) acc[nb] = mfma32(da[cq], cols.get(tQ, 16 * cq, nb), acc[nb]);
-      KNAP_STREAM_READS(2 * C::MB * C::NB, 2, 3);
-      KNAP_SCHED_FENCE();
-    };
-
-    __syncthreads();       // the previous item (or the schedule build) is done with every buffer
-    fetch_tile(0, stA);
-    commit_tile(0, stA);
-    fetch_tile(1, stB);
-    __syncthreads();
-
-    // step t: the dV wave works on tile t, the dK wave on tile t - 1, tile t + 1 sits in registers
-    // (`staged`) and tile t + 2 is requested (`incoming`)
-    auto step = [&](auto diag_tag, int t, Staged& incoming, const Staged& staged) {
-      fetch_tile(t + 2, incoming);         // past the end: an empty descriptor, every lane reads zero
-      if (role == 0) {
-        if (t < n_tiles) dv_step(diag_tag, t, t % C::NBUF);
-      } else {
-        if (t >= 1 && t <= n_tiles) dk_step(t - 1, (t - 1) % C::NBUF);
-      }
-      commit_tile((t + 1) % C::NBUF, staged);   // that buffer is free at step t, also when tile t + 1 is past the end
-      __syncthreads();     // P of tile t and tile t + 1 visible; tile t - 1 and P of tile t - 1 released
-    };
-    // steps 0 .. n_tiles.  The loop body is two unconditional steps (a step under a condition inside
-    // the loop would make the load counts inexact); an odd step left over is taken after it.
-    int t = 0;
-    if constexpr (!CAUSAL) {
-      for (; t + 1 <= n_tiles; t += 2) {
-        step(std::false_type{}, t, stA, stB);
-        step(std::false_type{}, t + 1, stB, stA);
-      }
-      if (t <= n_tiles) step(std::false_type{}, t, stA, stB);
-    } else {
-      // the two tiles that cross the diagonal come last (steps n_tiles - 2 and n_tiles - 1); the unmasked
-      // loop runs up to the even step at or below n_tiles - 2, the two to four steps after it take the mask
-      // (which hides nothing in a tile above the diagonal)
-      const int n_plain = max(0, n_tiles - 2) & ~1;
-      for (; t < n_plain; t += 2) {
-        step(std::false_type{}, t, stA, stB);
-        step(std::false_type{}, t + 1, stB, stA);
-      }
-      step(std::true_type{}, t, stA, stB);
-      step(std::true_type{}, t + 1, stB, stA);        // n_tiles >= 1: step n_plain + 1 exists
-      if (t + 2 <= n_tiles) step(std::true_type{}, t + 2, stA, stB);
-      if (t + 3 <= n_tiles) step(std::true_type{}, t + 3, stB, stA);
-    }
-
-    // this wave's rows of dV, or of dK (scaled): register r is key 8 (r / 4) + 4 hh + r % 4, lane is d
-    __bf16* dst = role == 0 ? dv : dk;
-    const float out_scale = role == 0 ? 1.0f : scale;
-#pragma unroll
-    for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kv = kv0 + 32 * pair + 8 * (r >> 2) + 4 * hh + (r & 3);
-        if (kv < L)
-          dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[nb][r] * out_scale);
-      }
-    if constexpr (CAUSAL) {
-      if (sub == 0 && it.tile != kv_tiles - 1 - it.tile) {   // not the middle tile of an odd count
-        sub = 1;
-        goto second_tile_of_pair;
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// dK/dV kernel, bidirectional mask: 64 key rows per wave pair.
-//
-// Same roles as above (dV wave: S, P, dV; dK wave, one tile behind: dP, dS, dK), but a pair owns 64
-// key rows (two 32-row blocks) of a 256-row key/value tile and a step covers 32 query rows.  Every
-// fragment of Q or dO that a wave reads from LDS, row-wise for S / dP and transposed for dV / dK, then
-// feeds TWO MFMAs, one per key block: 512 bytes of LDS operand per MFMA instead of 1024.  The registers
-// just allow it because the accumulators sit on the key side: per wave 128 (dV or dK, 64 x d fp32) + 64
-// (its K or V rows) + 32 (scores of a step) + operands in flight, within the 256 of two waves per SIMD
-// (every base address in scalar registers, every LDS address formed next to its read).
+// Every fragment of Q or dO that a wave reads from LDS, row-wise for S / dP and transposed for dV /
+// dK, feeds TWO MFMAs, one per key block: 512 bytes of LDS operand per MFMA.  The registers just allow
+// it because the accumulators sit on the key side: per wave 128 (dV or dK, 64 x d fp32) + 64 (its K or
+// V rows) + 32 (scores of a step) + operands in flight, within the 256 of two waves per SIMD (every
+// base address in scalar registers, every LDS address formed next to its read).
 //
 // Query-side tiles (32 rows of Q and dO, their LSE in base 2 and delta) go global -> LDS
 // asynchronously, DEPTH tiles ahead, into a ring of DEPTH + 2 buffers (being filled / dV role / dK
@@ -360,6 +66,13 @@ __global__ __launch_bounds__(BwdCfg<D>::THREADS, 2) void attn_bwd_dkdv_kernel(
 // issues the same number per tile).  Rows past the end of the sequence arrive as zeros in all four
 // (empty buffer descriptor): P = exp2(0 - 0) = 1 there, but dO = 0 and dP - delta = 0, so they add
 // nothing to dV or dK.
+//
+// CAUSAL (query i sees keys 0..i): a key tile starting at row kv0 only meets the queries from row kv0
+// on.  The walk over them runs BACKWARDS, from the sequence's last query tile down to the eight tiles
+// that cross the diagonal (which get the mask): workgroups on different key tiles of one (sequence,
+// head) then read the same query tiles at the same time, as they do without the mask, instead of each
+// starting at its own diagonal.  Work items are pairs of key tiles of equal total cost (see
+// build_schedule).
 // ---------------------------------------------------------------------------
 template <int D>
 struct Bwd2Cfg {
@@ -413,7 +126,7 @@ struct ColReaderX {
   }
 };
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
@@ -433,7 +146,7 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
   __shared__ __attribute__((aligned(256))) float sSink[64];
   __shared__ __attribute__((aligned(16))) u32x4 sP[4][2][2 * C::KB][64];
 
-  const int n_items = build_schedule<C::BN, C::THREADS, false>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
+  const int n_items = build_schedule<C::BN, C::THREADS, CAUSAL>(cu, n_seq, H, s_order, s_start, reinterpret_cast<int*>(&sP[0][0][0][0]));
   const int T = cu[n_seq];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -459,19 +172,32 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
   for (int round = 0; round * (int)gridDim.x < n_items; ++round) {
     const int w = serpentine_item(round, wg, (int)gridDim.x);
     if (w >= n_items) continue;
-    WorkItem it = decode_item<C::BN, false>(w, cu, n_seq, s_order, s_start);
+    WorkItem it = decode_item<C::BN, CAUSAL>(w, cu, n_seq, s_order, s_start);
     // head and tile come out of a division, i.e. of vector instructions: say that they are wave-uniform, so
     // that every base address below lives in scalar registers
     it.head = __builtin_amdgcn_readfirstlane(it.head);
     it.tile = __builtin_amdgcn_readfirstlane(it.tile);
     const int L = it.len;
     const size_t head_off = (size_t)it.head * D;
-    const int kv0 = it.tile * C::BN;
-    const __bf16* q_base = q + (size_t)it.row0 * row_stride + head_off;
-    const __bf16* do_base = dout + (size_t)it.row0 * row_stride + head_off;
-    const float* lse_base = lse2 + (size_t)it.head * T + it.row0;
-    const float* delta_base = delta + (size_t)it.head * T + it.row0;
-    const int n_tiles = (L + C::BM - 1) / C::BM;
+    // CAUSAL: the item is the pair of key tiles {p, kv_tiles - 1 - p} (equal cost together, see build_schedule),
+    // the one that meets more queries first; the middle tile of an odd count stands alone
+    const int kv_tiles = (L + C::BN - 1) / C::BN;
+    int sub = 0;
+  second_tile_of_pair:;     // CAUSAL only: jumped back to once, from the end of the first tile
+    const int kv_tile = (!CAUSAL || sub == 0) ? it.tile : kv_tiles - 1 - it.tile;
+    const int kv0 = kv_tile * C::BN;
+    // queries this key tile meets: rows q_first .. L - 1 of the sequence; tiles and rows below count from q_first
+    const int q_first = CAUSAL ? kv0 : 0;
+    const int Lq = L - q_first;
+    const __bf16* q_base = q + (size_t)(it.row0 + q_first) * row_stride + head_off;
+    const __bf16* do_base = dout + (size_t)(it.row0 + q_first) * row_stride + head_off;
+    const float* lse_base = lse2 + (size_t)it.head * T + it.row0 + q_first;
+    const float* delta_base = delta + (size_t)it.head * T + it.row0 + q_first;
+    const int n_tiles = (Lq + C::BM - 1) / C::BM;
+    // CAUSAL: step t works on query tile n_tiles - 1 - t: the walk runs BACKWARDS, from the sequence's last
+    // query tile down to the eight tiles that cross the diagonal of this key tile (which get the mask), so
+    // that workgroups on different key tiles of one (sequence, head) read the same query tiles at the same
+    // time, as they do without the mask
 
     __syncthreads();
 
@@ -495,8 +221,14 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
       for (int nb = 0; nb < C::NB; ++nb) acc[kb][nb] = zero16();
 
     auto issue_tile = [&](int t, __bf16* tQ, __bf16* tdO, float* tLse, float* tDelta) {
-      const int q0 = t * C::BM;
-      const int n_rows = max(0, min(L - q0, C::BM));
+      int q0, n_rows;
+      if constexpr (CAUSAL) {
+        q0 = max(0, n_tiles - 1 - t) * C::BM;
+        n_rows = t < n_tiles ? min(Lq - q0, C::BM) : 0;
+      } else {
+        q0 = t * C::BM;
+        n_rows = max(0, min(L - q0, C::BM));
+      }
       const auto rq = make_rsrc(q_base + (size_t)q0 * row_stride, (uint32_t)n_rows * row_bytes);
       const auto rd = make_rsrc(do_base + (size_t)q0 * row_stride, (uint32_t)n_rows * row_bytes);
       if constexpr (D == 128) {
@@ -577,10 +309,26 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
         lq[cq][0] = *reinterpret_cast<const f32x4*>(&tLse[16 * cq + 4 * hh]);
         lq[cq][1] = *reinterpret_cast<const f32x4*>(&tLse[16 * cq + 8 + 4 * hh]);
       };
+      // CAUSAL, tiles that cross the diagonal (the first eight from q_first): a query before this lane's key
+      // gets P = 0.  Counted from the tile's first query, the lane's key of block kb is the first one that
+      // query `first_seen[kb]` sees.
+      bool diag = false;
+      int first_seen[C::KB];
+      if constexpr (CAUSAL) {
+        diag = n_tiles - 1 - t < C::BN / C::BM;
+#pragma unroll
+        for (int kb = 0; kb < C::KB; ++kb) first_seen[kb] = 64 * pair + 32 * kb + l32 - (n_tiles - 1 - t) * C::BM - 4 * hh;
+      }
       auto exp_slice = [&](int cq, int kb, int half) {
         float p[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) p[e] = fast_exp2(__builtin_fmaf(s[kb][8 * cq + 4 * half + e], c, -lq[cq][half][e]));
+        if constexpr (CAUSAL) {
+          if (diag) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] = 8 * (2 * cq + half) + e < first_seen[kb] ? 0.f : p[e];
+          }
+        }
         ph[cq][kb][half] = pack4(p[0], p[1], p[2], p[3]);
         if (half == 1) {
           pa[cq][kb] = join(ph[cq][kb][0], ph[cq][kb][1]);
@@ -599,7 +347,6 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
       });
       second_product(tdO, cb, 1, pa[1], [&](int) {});
     };
-    // dK wave, tile u: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
     // dK wave, tile u: dP, dS = P (dP - delta) with the partner's P, dK += dS^T Q
     auto dk_step = [&](int u, const __bf16* tQ, const __bf16* tdO, const float* tDelta) {
       const int rb = rows.fresh();
@@ -699,6 +446,12 @@ __global__ __launch_bounds__(Bwd2Cfg<D>::THREADS, 2) void attn_bwd_dkdv64_kernel
           if (kv < L)
             dst[(size_t)(it.row0 + kv) * row_stride + head_off + 32 * nb + l32] = (__bf16)(acc[kb][nb][r] * out_scale);
         }
+    if constexpr (CAUSAL) {
+      if (sub == 0 && it.tile != kv_tiles - 1 - it.tile) {   // not the middle tile of an odd count
+        sub = 1;
+        goto second_tile_of_pair;
+      }
+    }
   }
 }
 
@@ -949,15 +702,9 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-  if constexpr (CAUSAL) {
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, true>), dim3(grid_dkdv), dim3(BwdCfg<D>::THREADS), dyn, stream,
-                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse,
-                       (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
-  } else {
-    hipLaunchKernelGGL((attn_bwd_dkdv64_kernel<D>), dim3(grid_dkdv), dim3(Bwd2Cfg<D>::THREADS), dyn, stream,
-                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout,
-                       (const float*)lse2, (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
-  }
+  hipLaunchKernelGGL((attn_bwd_dkdv64_kernel<D, CAUSAL>), dim3(grid_dkdv), dim3(Bwd2Cfg<D>::THREADS), dyn, stream,
+                     (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout,
+                     (const float*)lse2, (const float*)delta, cu, n_seq, H, scale, (__bf16*)dk, (__bf16*)dv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev_start && ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
@@ -985,11 +732,8 @@ static int occupancy_of(const void* fn, int threads = kThreads) {
   return n;
 }
 
-int bwd_dkdv_workgroups_per_cu(int d, bool causal) {
-  if (causal)
-    return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv_kernel<64, true> : (const void*)attn_bwd_dkdv_kernel<128, true>,
-                        BwdCfg<128>::THREADS);
-  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv64_kernel<64> : (const void*)attn_bwd_dkdv64_kernel<128>,
+int bwd_dkdv_workgroups_per_cu(int d) {
+  return occupancy_of(d == 64 ? (const void*)attn_bwd_dkdv64_kernel<64, false> : (const void*)attn_bwd_dkdv64_kernel<128, false>,
                       Bwd2Cfg<128>::THREADS);
 }
 

@@ -32,7 +32,7 @@ hipError_t launch_ulysses_plan(const int32_t* cu, int n_seq, int g, int T, int32
 
 // resident workgroups per compute unit of the persistent kernels
 int fwd_workgroups_per_cu(int d);
-int bwd_dkdv_workgroups_per_cu(int d, bool causal);
+int bwd_dkdv_workgroups_per_cu(int d);
 int bwd_dq_workgroups_per_cu(int d);
 
 }  // namespace knap
