@@ -8,6 +8,9 @@ dV = P^T dO, dP = dO V^T, D_i = dO_i . O_i, dS = P (dP - D), dQ = scale dS K, dK
 * Q = 0: P uniform as well.  dK = 0 exactly, dQ_i = (scale / L) (K^T V - L kbar vbar^T) dO_i.
 * constant V rows (V_j = v): O = v bit for bit (v is a bf16 value and the weights sum to one), dP_ij = D_i
   for every j, so dS = 0 and dQ = dK = 0 up to float32 rounding of dP - D; sum_j dV_j = sum_i dO_i.
+* causal mask with K = 0 or Q = 0: P_ij = 1/(i+1) for j <= i; O is the running mean of V, LSE_i = ln(i+1), and
+  dQ, dK, dV follow from prefix and suffix sums (written out in causal_closed_forms.py, which the CPU suite
+  checks against the oracle's causal mode): every element of the causal entry points' outputs on configs 2-4.
 * periodic sequence: if q, k, v, dO of a sequence of length L = m p repeat with period p, every key of the
   period-p problem appears m times with the same score, so P_ij(L) = P_i'j'(p) / m and O, dQ, dK, dV of row
   i equal those of row i mod p of the period-p problem; LSE(L) = LSE(p) + ln m.  The period-p problem is
@@ -26,6 +29,7 @@ import pytest
 from knap_inputs import BagSpec, bf16_bits_to_f32, config_bag, cu_seqlens_of, make_qkv_dout
 from oracle import attention as A
 
+from causal_closed_forms import causal_zero_score_reference
 from gpu_util import GpuRun, say
 
 pytestmark = pytest.mark.gpu
@@ -239,3 +243,40 @@ def test_periodic_sequence_with_a_period_that_no_tile_divides():
         assert e_out <= FWD_TOL and e_lse <= LSE_TOL
         for n in errs:
             assert errs[n] <= BWD_TOL, (n, errs[n])
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("zero", ["k", "q"])
+@pytest.mark.parametrize("config", [2, 3, 4])
+def test_causal_zero_scores_every_element(config, zero):
+    """The causal entry points at full size with K = 0 (or Q = 0): every row of every head against the closed
+    form.  The first rows of a sequence see one or two keys and return single v entries, so the forward bar
+    is relative there (2^-8 |ref|, one bf16 rounding)."""
+    import torch
+    bag = _bags()[config]
+    T, H, d = bag.total_tokens, bag.H, bag.d
+    dev = {n: _randn_bf16((T, H, d), bag.seed + 40 + i) for i, n in enumerate(("q", "k", "v", "dout"))}
+    dev[zero] = torch.zeros((T, H, d), dtype=torch.bfloat16, device="cuda")
+    run = GpuRun(bag, device_tensors=dev, causal=True)
+    a = run.attn
+    assert int(torch.count_nonzero(a.dq if zero == "k" else a.dk)) == 0     # every term multiplies a zero row
+    cu = [int(c) for c in run.cu]
+    worst = {"out": 0.0, "lse": 0.0, "dq": 0.0, "dk": 0.0, "dv": 0.0}
+    for s in range(len(cu) - 1):
+        sl = slice(cu[s], cu[s + 1])
+        q, k, v, do = (dev[n][sl].double() for n in ("q", "k", "v", "dout"))
+        out, lse, dq, dk, dv = causal_zero_score_reference(q, k, v, do, bag.scale)
+        err = (a.out[sl].double() - out).abs()
+        err = torch.where(err <= 2.0 ** -8 * out.abs(), torch.zeros_like(err), err)
+        worst["out"] = max(worst["out"], float(err.max()))
+        worst["lse"] = max(worst["lse"], float((a.lse[:, sl].double() - lse).abs().max()))
+        worst["dv"] = max(worst["dv"], _rel(a.dv[sl].double(), dv))
+        if zero == "k":
+            worst["dk"] = max(worst["dk"], _rel(a.dk[sl].double(), dk))
+        else:
+            worst["dq"] = max(worst["dq"], _rel(a.dq[sl].double(), dq))
+        del q, k, v, do, out, lse, dq, dk, dv, err
+    say(f"[closed form] {bag.name} causal {zero.upper()}=0: " + " ".join(f"{n} {e:.3e}" for n, e in worst.items()))
+    assert worst["out"] <= FWD_TOL and worst["lse"] <= LSE_TOL
+    for n in ("dq", "dk", "dv"):
+        assert worst[n] <= BWD_TOL, (n, worst[n])
