@@ -424,6 +424,43 @@ def test_causal_post_ulysses_share_sampled():
         _invariants(run, s, s % 3)
 
 
+@pytest.mark.timeout(300)
+def test_causal_image_video_bag_sampled():
+    """Benchmark config 2 at full size under the causal mask."""
+    bag = config_bag(2)
+    run = GpuRun(bag, causal=True)
+    longest = int(np.argmax(bag.seq_lens))
+    shortest = int(np.argmin(bag.seq_lens))
+    _sampled_compare(run, longest, 9, n_rows=48, n_cols=48, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, shortest, 17, n_rows=48, n_cols=48, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _sampled_compare(run, 8, 2, n_rows=32, n_cols=24, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    for s in (longest, shortest, 0):
+        _invariants(run, s, 13)
+
+
+@pytest.mark.timeout(400)
+def test_causal_skewed_bag_sampled():
+    """Benchmark config 3 at full size under the causal mask, the 65536-token sequence in the middle of the
+    bag (256 key tiles in 128 pairs, peaky keys): sampled query rows and key rows of it, and two short
+    sequences against the full oracle."""
+    bag = config_bag(3, long_position="middle")
+    run = GpuRun(bag, causal=True)
+    s_long = bag.seq_lens.index(65536)
+    _sampled_compare(run, s_long, 11, n_rows=40, n_cols=16, causal=True, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
+    _invariants(run, s_long, 4)
+    cu = [int(c) for c in run.cu]
+    for s, h in ((0, 5), (len(bag.seq_lens) - 1, 22)):
+        sl = slice(cu[s], cu[s + 1])
+        Q, K_, V, dO = (run.host(n, sl, h) for n in ("q", "k", "v", "dout"))
+        O, LSE = A.attn_fwd_dense(Q, K_, V, bag.scale, causal=True)
+        dQ, dK, dV = A.attn_bwd_dense(Q, K_, V, dO, bag.scale, causal=True)
+        err = np.abs(run.host("out", sl, h) - O)
+        assert np.all(err <= np.maximum(FWD_TOL, 2.0 ** -8 * np.abs(O))), (s, h, float(err.max()))
+        assert np.max(np.abs(run.lse[h, sl] - LSE)) <= LSE_TOL_FEW_KEYS
+        for name, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
+            assert rel_fro(run.host(name, sl, h), ref) <= BWD_TOL, (name, s, h)
+
+
 def test_causal_repeatable_and_independent_of_other_sequences():
     """Bitwise repeatable (no floating-point atomics in the causal path either), and a sequence's
     results do not change when the other sequences of the bag do."""
