@@ -76,8 +76,10 @@ def test_tiny_bag_full_oracle():
 
 @pytest.mark.parametrize("d", [64, 128])
 def test_ragged_lengths_span_tiles_and_tails(d):
-    # lengths around every tile boundary in use (32, 64, 128), zero-length and single-token sequences
-    lens = [1, 2, 31, 0, 33, 63, 64, 65, 127, 128, 129, 0, 191, 257, 300, 513, 1]
+    # lengths around every tile boundary in use (32-row query steps and 256-row key tiles of the dK/dV kernel,
+    # 64-key and 128-query tiles of the others), query-step counts of every residue modulo the five-buffer
+    # ring, zero-length and single-token sequences
+    lens = [1, 2, 31, 0, 33, 63, 64, 65, 127, 128, 129, 0, 191, 255, 256, 257, 300, 511, 512, 513, 769, 1]
     bag = BagSpec("ragged", lens, H=3, d=d, seed=777 + d)
     run = _full_compare(bag, strict_fwd=False, lse_tol=LSE_TOL_FEW_KEYS)
     # rows of zero-length sequences do not exist; every row < T was written (no NaN canary left)
@@ -362,9 +364,11 @@ def test_causal_tiny_bag_full_oracle():
 
 @pytest.mark.parametrize("d", [64, 128])
 def test_causal_ragged_lengths_around_every_tile_boundary(d):
-    # query tiles are 128 rows, key tiles 64 / 128: lengths on both sides of each multiple, pairs of
-    # tiles with and without a middle tile (odd and even tile counts), zero-length and 1-token sequences
-    lens = [1, 2, 63, 64, 65, 0, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 385, 513, 640, 1]
+    # query tiles are 128 rows (32-row steps in the dK/dV kernel), key tiles 64 / 256: lengths on both sides of
+    # each multiple, pairs of tiles with and without a middle tile (odd and even tile counts, up to five
+    # 256-row key tiles), zero-length and 1-token sequences
+    lens = [1, 2, 63, 64, 65, 0, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 385, 511, 512, 513, 640,
+            769, 1024, 1025, 1]
     run = _full_compare(BagSpec("causal_ragged", lens, H=3, d=d, seed=1777 + d), strict_fwd=False, causal=True,
                         lse_tol=LSE_TOL_FEW_KEYS)
     assert np.all(np.isfinite(to_f64(run.out_bits))) and np.all(np.isfinite(run.lse))
