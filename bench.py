@@ -90,6 +90,13 @@ def flops_bwd(bag, causal: bool = False) -> float:
     return 10.0 * bag.H * bag.d * score_count(bag, causal)
 
 
+def tile_padded_sum_l2(seq_lens) -> float:
+    """sum(L^2) with every sequence padded to the kernels' tiles: the forward and the dQ kernel work on whole
+    128-row query tiles (10 of the 18 units of matrix work a step issues), the dK/dV kernel on whole 256-row
+    key tiles (8 of 18).  Equals sum(L^2) when every L is a multiple of 256."""
+    return float(sum(L * ((10.0 / 18.0) * 128 * -(-L // 128) + (8.0 / 18.0) * 256 * -(-L // 256)) for L in seq_lens))
+
+
 def flops_dkdv_kernel(bag, causal: bool = False) -> float:
     """Algorithmic FLOPs credited to the dK/dV kernel: the recompute of S and dP (4) plus dV and dK (4).
     The dQ kernel recomputes S and dP a second time; that repeat is not algorithmic work and is
@@ -508,7 +515,8 @@ def run_fit(args):
                 dev = device_inputs_fast(bag)
                 r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev, causal=causal)
                 evals.append({"config": ci, "seed_offset": so, "n_seq": len(bag.seq_lens), "T": bag.total_tokens,
-                              "sum_l2": bag.sum_l2, "ms": r["gpu_ms_per_step"], "role": "evaluation"})
+                              "sum_l2": bag.sum_l2, "sum_l2_tile_padded": tile_padded_sum_l2(bag.seq_lens),
+                              "ms": r["gpu_ms_per_step"], "role": "evaluation"})
                 log(f"[fit] {fam} cfg{ci}/{so}: measured {r['gpu_ms_per_step']:.3f} ms")
                 del dev, r
                 torch.cuda.empty_cache()
@@ -529,8 +537,12 @@ def run_fit(args):
             e["rel_resid"] = abs(e["ms"] - e["pred_ms"]) / e["ms"]
             e["pred_ms_with_intercept"] = a3 * e["sum_l2"] + b3 * e["T"] + c3
             e["rel_resid_with_intercept"] = abs(e["ms"] - e["pred_ms_with_intercept"]) / e["ms"]
+            # diagnostic: the same a, b (no refit) with the kernels' padding of every sequence to whole tiles
+            e["pred_ms_tile_padded"] = a * e["sum_l2_tile_padded"] + b * e["T"]
+            e["rel_resid_tile_padded"] = abs(e["ms"] - e["pred_ms_tile_padded"]) / e["ms"]
             log(f"[fit] {fam} cfg{e['config']}/{e['seed_offset']}: measured {e['ms']:.3f} ms, model {e['pred_ms']:.3f} ms, "
-                f"resid {e['rel_resid'] * 100:.1f}% (with intercept {e['rel_resid_with_intercept'] * 100:.1f}%)")
+                f"resid {e['rel_resid'] * 100:.1f}% (with intercept {e['rel_resid_with_intercept'] * 100:.1f}%, "
+                f"tile-padded {e['rel_resid_tile_padded'] * 100:.1f}%)")
         report["families"][fam] = {"a_ms_per_token2": a, "b_ms_per_token": b, "calibration_max_rel_resid": resid,
                                    "with_intercept": {"a": float(a3), "b": float(b3), "c_ms": float(c3)},
                                    "calibration": rows, "evaluation": evals}

@@ -30,3 +30,10 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert p.returncode != 0
     assert "--gpus must be 1" in p.stderr
+
+
+def test_tile_padded_score_count():
+    assert bench.tile_padded_sum_l2([256, 512, 1024]) == float(256 ** 2 + 512 ** 2 + 1024 ** 2)
+    # 100 tokens: one 128-row query tile (10/18 of the work) and one 256-row key tile (8/18)
+    assert abs(bench.tile_padded_sum_l2([100]) - 100 * (10 / 18 * 128 + 8 / 18 * 256)) < 1e-9
+    assert bench.tile_padded_sum_l2([300]) > 300.0 ** 2
