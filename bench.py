@@ -393,6 +393,32 @@ def run_default(args):
     print(json.dumps(out), flush=True)
 
 
+def run_single_length(args):
+    """One single-length bag of the calibration family (n = 65536 / L sequences of L tokens, 24 heads of 128):
+    step time and the split over the three kernels, for the cost of a work item on short sequences."""
+    from knap_inputs import BagSpec
+    ev = HipEvents()
+    L = args.single_length
+    H, d, tokens = 24, 128, 65536
+    n = max(1, tokens // L)
+    bag = BagSpec(f"single_length_{L}", [L] * n, H=H, d=d, seed=5000 + L)
+    dev = [device_inputs_fast(bag), device_inputs_fast(bag, seed=1)]
+    r = time_bag(bag, dev, steps=args.steps, warmup=args.warmup, ev=ev, causal=args.causal)
+    ms = r["gpu_ms_per_step"]
+    fl = flops_fwd(bag, args.causal) + flops_bwd(bag, args.causal)
+    dq_ms = r["bwd_ms"] - r["bwd_main_ms"]
+    log(f"[single] {n} x L={L}: {ms:.3f} ms/step = {fl / ms / 1e9:.1f} TF/s; fwd {r['fwd_ms']:.3f} ms, "
+        f"dQ kernel (with delta, queue reset) {dq_ms:.3f} ms, dK/dV kernel {r['bwd_main_ms']:.3f} ms")
+    out = {"metric": "varlen attention fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak", "value": round(fl / ms / 1e9, 3),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{n} sequences of {L} tokens" + (" (causal mask)" if args.causal else ""),
+                      "n_seq": n, "total_tokens": n * L, "H": H, "d": d},
+           "pct_of_bf16_mfma_peak": round(100.0 * fl / ms / 1e9 / PEAK_BF16_TFLOPS, 2),
+           "fwd_ms": round(r["fwd_ms"], 4), "dq_kernel_ms": round(dq_ms, 4), "dkdv_kernel_ms": round(r["bwd_main_ms"], 4)}
+    print(json.dumps(out), flush=True)
+
+
 def run_sim(args):
     """Second workload: the paper's own simulator streams (Sec. 4.1 data codes; the `joint` and `mixed_res`
     workloads of Table 1 on 32 GPUs at 24 heads of 128).  The cost model is fitted on single-length bags in this
@@ -744,6 +770,8 @@ def main():
     ap.add_argument("--fit", action="store_true", help="cost-model calibration and residual report")
     ap.add_argument("--sim", action="store_true",
                     help="time one-GPU bags drawn from the paper's simulator streams (second workload, not the headline)")
+    ap.add_argument("--single-length", type=int, default=None, metavar="L",
+                    help="time one bag of 65536 / L sequences of L tokens (24 heads of 128) with the split over the kernels")
     ap.add_argument("--ulysses", action="store_true",
                     help="time the local data movement around the Ulysses all-to-alls (not the headline workload)")
     ap.add_argument("--fit-draws", type=int, default=12, help="evaluation bags per benchmark configuration in --fit")
@@ -766,6 +794,11 @@ def main():
         run_sim(args)
     elif args.ulysses:
         run_ulysses(args)
+    elif args.single_length is not None:
+        if args.single_length < 1 or args.single_length > 65536:
+            print("bench.py: --single-length takes a length from 1 to 65536", file=sys.stderr)
+            sys.exit(2)
+        run_single_length(args)
     else:
         run_default(args)
 
