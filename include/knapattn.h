@@ -53,7 +53,8 @@ extern "C" {
  *
  * Supported: d in {64, 128}; 0 <= n_seq <= KNAP_MAX_SEQS; H >= 1; scale positive
  * and finite; T < 2^31.
- * n_seq == 0 succeeds and enqueues nothing.
+ * n_seq == 0 succeeds and enqueues nothing.  With n_seq > 0 every pointer must be
+ * non-null even if all sequences are empty (T = 0): the host cannot see T.
  * ------------------------------------------------------------------------ */
 
 /* out = softmax(scale * q k^T) v per (sequence, head); also writes lse.
