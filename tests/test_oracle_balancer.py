@@ -197,3 +197,15 @@ def test_fit_recovers_known_constants():
     noisy = t * (1.0 + 0.01 * rng.standard_normal(t.shape))
     a3, b3, r3 = B.fit_cost_model(L * L, L, noisy)
     assert a3 == pytest.approx(a, rel=0.05) and b3 == pytest.approx(b, rel=0.05) and r3 < 0.05
+
+
+def test_bag_sequences_hand_case_keeps_original_order():
+    # six sequences dealt to three bags by hand: a bag's packed list is its members in the order they
+    # arrived, duplicates of a length stay apart, an unused bag is empty
+    lens = [5, 3, 8, 3, 1, 7]
+    bag_of = [1, 0, 1, 1, 0, 1]
+    assert B.bag_sequences(lens, bag_of, 0) == [3, 1]
+    assert B.bag_sequences(lens, bag_of, 1) == [5, 8, 3, 7]
+    assert B.bag_sequences(lens, bag_of, 2) == []
+    # the bags partition the multiset of lengths
+    assert sorted(B.bag_sequences(lens, bag_of, 0) + B.bag_sequences(lens, bag_of, 1)) == sorted(lens)
